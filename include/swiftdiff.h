@@ -1,0 +1,195 @@
+/*
+ * swiftdiff.h — C ABI of the MI355X (gfx950) kernels for the base-model denoising hot
+ * path of SwiftDiffusion (arXiv 2407.02031): the LoRA-augmented SDXL spatial-transformer
+ * block run on the classifier-free-guidance pair, and in-place LoRA patching.
+ *
+ * Conventions common to every call
+ * --------------------------------
+ *  - Return value: SD_OK (0) or a negative SD_E* code; sd_last_error() gives the text of
+ *    the most recent failure on the calling thread.  Nothing is printed, nothing aborts.
+ *  - "device" pointers are HIP device memory owned by the caller, 16-byte aligned, dense
+ *    row-major.  "host" pointers are ordinary host memory read during the call only.
+ *  - bf16 tensors are passed as uint16_t bit patterns.  Accumulation is always fp32.
+ *  - Weights are stored [out, in]; y = x W^T.  A LoRA adapter is A [r, in] (down) and
+ *    B [out, r] (up) with a scalar scale = alpha / r; r must be a multiple of 8.
+ *  - The library never allocates, frees or synchronises.  Scratch memory comes from the
+ *    caller's workspace `ws` (device, 256-byte aligned) of at least the size the matching
+ *    *_workspace_bytes query returns; all work is enqueued on `stream` (a hipStream_t).
+ *  - Same inputs give bit-identical outputs run to run (no atomics in reductions).
+ */
+#ifndef SWIFTDIFF_H
+#define SWIFTDIFF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SD_OK 0
+#define SD_EINVAL (-1)       /* null / misaligned pointer, bad dimension or flag            */
+#define SD_EUNSUPPORTED (-2) /* a shape the kernels do not cover (e.g. head dim != 64)      */
+#define SD_EWORKSPACE (-3)   /* workspace missing or too small                              */
+#define SD_EHIP (-4)         /* HIP runtime error; text in sd_last_error()                  */
+
+#define SD_BF16 0
+#define SD_F32 1
+
+#define SD_EPI_NONE 0
+#define SD_EPI_GEGLU 1
+
+/* One linear projection with an optional rank-r adapter (Section 2, "Low-Rank
+ * Adaptation": the patched weight is the base weight plus a rank-r product).
+ * All pointers are device memory; bias, A, B may be NULL (A and B together). */
+typedef struct sd_proj {
+    const uint16_t* W;    /* [N, K] bf16 (GEGLU: [2N, K], value rows first, gate rows second) */
+    const uint16_t* bias; /* [N] bf16 (GEGLU: [2N]) or NULL                                   */
+    const uint16_t* A;    /* [r, K] bf16 or NULL                                              */
+    const uint16_t* B;    /* [N, r] bf16 (GEGLU: [2N, r]) or NULL                             */
+    int32_t r;            /* adapter rank; 0 = none                                           */
+    float scale;          /* alpha / r                                                        */
+} sd_proj;
+
+/* Parameters of one transformer block (all device pointers, bf16). */
+typedef struct sd_block_params {
+    const uint16_t *ln1_g, *ln1_b; sd_proj q1, k1, v1, o1;   /* self-attention             */
+    const uint16_t *ln2_g, *ln2_b; sd_proj q2, k2, v2, o2;   /* cross-attention (k2,v2: [C, Dc]) */
+    const uint16_t *ln3_g, *ln3_b; sd_proj ff1, ff2;         /* GEGLU feed-forward          */
+} sd_block_params;
+
+/* Parameters of a spatial-transformer stack.  `blocks` is a HOST array of `depth` entries. */
+typedef struct sd_stack_params {
+    const uint16_t *gn_g, *gn_b;      /* GroupNorm(32) affine, [C]            */
+    sd_proj proj_in, proj_out;        /* Linear C -> C with bias, no adapter  */
+    const sd_block_params* blocks;    /* host array                           */
+    int32_t depth;
+} sd_stack_params;
+
+/* One weight matrix to patch (fp32, device pointers). */
+typedef struct sd_patch_desc {
+    float* W;         /* [out, in], patched in place                                    */
+    const float* A;   /* [r, in]                                                        */
+    const float* B;   /* [out, r]                                                       */
+    float* undo;      /* [out, in] record of W's bits before the patch; required        */
+    int32_t out, in, r;
+    float scale;
+} sd_patch_desc;
+
+const char* sd_last_error(void);
+int32_t sd_version(void);
+
+/* ---- lora_linear_fwd ------------------------------------------------------------------
+ * y = epi( LN?(x) W^T + bias + scale * (LN?(x) A^T) B^T ) + residual
+ * The unmerged form of Section 2's W' = W + A B applied to an input; the rank-r update
+ * runs inside the base GEMM's main loop (K extended by r).  With p->r == 0 it is the
+ * plain linear layer a patched (merged) weight needs.
+ *   x        device [M, K]; bf16, or fp32 when a LayerNorm is given (x_dtype = SD_F32)
+ *   ln_gamma, ln_beta  device [K] bf16 or both NULL (no LayerNorm); biased variance
+ *   residual device [M, N] of y_dtype or NULL; may alias y
+ *   y        device [M, N], y_dtype bf16 or fp32
+ *   epilogue SD_EPI_GEGLU: W, bias, B have 2N rows and y = value * gelu(gate) (exact erf
+ *            GELU; Section 4.3's fused GEGLU); residual must then be NULL
+ * K and p->r must be multiples of 8.  Errors: SD_EINVAL, SD_EWORKSPACE, SD_EHIP. */
+size_t sd_lora_linear_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t r, int32_t has_ln);
+int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj* p,
+                       const uint16_t* ln_gamma, const uint16_t* ln_beta, float ln_eps,
+                       const void* residual, void* y, int32_t y_dtype, int32_t epilogue,
+                       int32_t M, int32_t N, int32_t K,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* ---- attn_block_fwd -------------------------------------------------------------------
+ * y = x + out( attention( q(LN x), k(src), v(src) ) ),  src = LN x (ctx NULL: latent
+ * self-attention) or ctx (cross-attention to the text tokens that guide every denoising
+ * step, Section 2).  Attention is softmax(q k^T / 8) v per (sample, head), head dim 64,
+ * no mask; scores are never written to memory.
+ *   x, y     device [Bn, T, C] of io_dtype (bf16 or fp32); y may alias x
+ *   ctx      device [Bn, Tc, Dc] bf16 or NULL
+ *   q,k,v,o  host structs; q,o: [C, C]; k,v: [C, C] (self) or [C, Dc] (cross)
+ * Requires C == 64 * heads, C and Dc multiples of 8. */
+size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max);
+int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype,
+                      const uint16_t* ctx, int32_t Tc, int32_t Dc,
+                      const uint16_t* ln_gamma, const uint16_t* ln_beta, float ln_eps,
+                      const sd_proj* q, const sd_proj* k, const sd_proj* v, const sd_proj* o,
+                      int32_t Bn, int32_t T, int32_t C, int32_t heads,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ---- attention_fwd (helper) -----------------------------------------------------------
+ * out[b, t, h*64 + d] = softmax_k(q[b,t,h,:] . k[b,k,h,:] / 8) v[b,k,h,d]
+ *   q   device [Bn, Tq, C] bf16;  k device [Bn, Tk, C] bf16
+ *   vt  device [C, Bn * Tkp] bf16: V transposed, sample b's keys at columns
+ *       [b*Tkp, b*Tkp + Tk), Tkp = Tk rounded up to a multiple of 8
+ *   out device [Bn, Tq, C] bf16 */
+int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* vt, uint16_t* out,
+                     int32_t Bn, int32_t Tq, int32_t Tk, int32_t C, int32_t heads, void* stream);
+
+/* ---- ff_block_fwd (helper) ------------------------------------------------------------
+ * y = x + ff2( geglu( ff1( LN x ) ) );  ff1: [2F, C] with bias, ff2: [C, F] with bias. */
+size_t sd_ff_block_workspace_bytes(int32_t M, int32_t C, int32_t F, int32_t r_max);
+int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype,
+                    const uint16_t* ln_gamma, const uint16_t* ln_beta, float ln_eps,
+                    const sd_proj* ff1, const sd_proj* ff2, int32_t M, int32_t C, int32_t F,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* ---- groupnorm_fwd (helper) -----------------------------------------------------------
+ * Token-major GroupNorm: x, y device [Bn, T, C] bf16; statistics per (sample, group of
+ * C/groups adjacent channels) over all tokens, biased variance, per-channel affine. */
+size_t sd_groupnorm_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t groups);
+int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
+                     int32_t Bn, int32_t T, int32_t C, int32_t groups, float eps,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---- spatial_transformer_fwd ----------------------------------------------------------
+ * The whole hot path on the guidance pair (Section 3.3: both latents in one batch):
+ * y = proj_out( blocks( proj_in( GroupNorm32(x) ) ) ) + x, each block = self-attention,
+ * cross-attention, GEGLU feed-forward, each behind a LayerNorm and with a residual.
+ * The residual stream is kept in fp32 inside the call.
+ *   x, y device [Bn, T, C] bf16;  ctx device [Bn, Tc, Dc] bf16;  p host struct. */
+size_t sd_spatial_transformer_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max);
+int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx, const sd_stack_params* p,
+                               uint16_t* y, int32_t Bn, int32_t T, int32_t C, int32_t heads,
+                               int32_t Tc, int32_t Dc, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- multi_lora_linear_fwd ------------------------------------------------------------
+ * Several requests' rows stacked in one matrix, each row segment with its own adapter
+ * (the batched multi-LoRA operators of Section 7 applied per request):
+ *   y[rows of segment i] = x W^T + bias + scales[a] * (x A_a^T) B_a^T,  a = seg_adapter[i]
+ * (a = -1: no adapter).  Segments are contiguous, ordered, and cover [0, M).
+ *   A_ptrs, B_ptrs  host arrays of `nadapters` device pointers (A_a [ranks[a], K],
+ *                   B_a [N, ranks[a]], bf16);  ranks, scales host arrays
+ *   seg_offsets     host [nseg + 1], seg_adapter host [nseg] */
+size_t sd_multi_lora_linear_workspace_bytes(int32_t M, int32_t r_max);
+int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, const uint16_t* bias,
+                             const uint16_t* const* A_ptrs, const uint16_t* const* B_ptrs,
+                             const int32_t* ranks, const float* scales,
+                             const int32_t* seg_offsets, const int32_t* seg_adapter,
+                             int32_t nseg, int32_t nadapters, uint16_t* y,
+                             int32_t M, int32_t N, int32_t K,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/* ---- lora_patch / lora_unpatch --------------------------------------------------------
+ * Section 4.2, "Efficient LoRA patching": the adapter is merged into the base parameters
+ * in place, W <- fl32(W + fl32(scale * fl32(B A))), and taken off after the request.
+ * Taking it off must give back W's exact bits, which subtraction cannot do, so the patch
+ * pass also writes W's old bits to `undo` and unpatch copies them back.
+ *
+ * A plan is built once on the host from the descriptor list (validates it, splits every
+ * matrix into tiles), uploaded by the caller, and reused by patch and unpatch:
+ *   sd_patch_plan_bytes(n)            size of the plan for n matrices
+ *   sd_patch_plan_build(descs, n, plan_host, bytes, &tiles)   descs, plan_host: host
+ *   sd_lora_patch(plan_dev, n, tiles, stream)     one grouped launch over all matrices
+ *   sd_lora_unpatch(plan_dev, n, tiles, stream)   W <- undo, bit-exact
+ * Calling unpatch without a preceding patch on the same undo buffers copies whatever the
+ * buffers hold; the library cannot detect that.  Ordering against kernels that read W on
+ * other streams is the caller's job (events). */
+size_t sd_patch_plan_bytes(int32_t n);
+int sd_patch_plan_build(const sd_patch_desc* descs, int32_t n, void* plan_host, size_t plan_bytes,
+                        int64_t* total_tiles);
+int sd_lora_patch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
+int sd_lora_unpatch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIFTDIFF_H */

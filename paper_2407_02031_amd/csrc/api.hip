@@ -1,0 +1,465 @@
+// C-ABI entry points: argument checks, workspace carving, and the composition of the
+// kernels into projections, attention sub-layers, the feed-forward sub-layer and the whole
+// spatial-transformer stack.  Host code only; every arithmetic step runs in the kernels.
+#include "common.hpp"
+
+#include <string.h>
+#include <vector>
+
+namespace sd {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+int hip_fail(hipError_t e, const char* what) {
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return SD_EHIP;
+}
+
+// ---------------------------------------------------------------------------------------
+// projection -> GEMM problems
+// ---------------------------------------------------------------------------------------
+struct ProjOut {
+    void* y; int64_t ldy; int y_f32;
+    const void* res; int64_t ldr;
+    bool transposed;    // store y^T: y[n * ldy + m]
+    int geglu_F;        // > 0: GEGLU epilogue, N == F
+};
+
+static int check_proj(const sd_proj* p, const char* name, int K) {
+    SD_REQUIRE(p && p->W, SD_EINVAL, "%s: projection or its W is null", name);
+    SD_REQUIRE(aligned16(p->W), SD_EINVAL, "%s: W not 16-byte aligned", name);
+    SD_REQUIRE(p->r >= 0 && p->r % 8 == 0, SD_EUNSUPPORTED, "%s: rank %d is not a multiple of 8", name, p->r);
+    if (p->r > 0) {
+        SD_REQUIRE(p->A && p->B, SD_EINVAL, "%s: rank %d but A or B is null", name, p->r);
+        SD_REQUIRE(aligned16(p->A) && aligned16(p->B), SD_EINVAL, "%s: A/B not 16-byte aligned", name);
+    }
+    SD_REQUIRE(K > 0 && K % 8 == 0, SD_EUNSUPPORTED, "%s: K=%d is not a positive multiple of 8", name, K);
+    return SD_OK;
+}
+
+static int push(GemmGroup& g, const GemmProblem& P, hipStream_t stream) {
+    if (g.n == GEMM_MAX_PROBLEMS) {   // group full: flush it, order within a stream is kept
+        int rc = launch_gemm_group(g, stream);
+        if (rc) return rc;
+        g.n = 0;
+    }
+    g.p[g.n++] = P;
+    return SD_OK;
+}
+
+// One projection y = x W^T (+ bias) (+ scale (x A^T) B^T) as GEMM problems: the
+// down-projection t = scale * x A^T (bf16 [M, r]) and the K-extended base GEMM.
+struct ProjCall {
+    const uint16_t* x; int64_t ldx; int M, K, N;
+    const sd_proj* p; uint16_t* tbuf; ProjOut o;
+};
+
+static int push_down(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
+    const sd_proj& p = *c.p;
+    if (p.r <= 0) return SD_OK;
+    GemmProblem D;
+    memset(&D, 0, sizeof(D));
+    D.p0 = c.x; D.ldp0 = c.ldx; D.q0 = p.A; D.ldq0 = c.K;
+    D.y = c.tbuf; D.ldy = p.r; D.Mp = c.M; D.N = p.r; D.K0 = c.K; D.K1 = 0; D.alpha = p.scale;
+    return push(g, D, stream);
+}
+
+static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
+    const sd_proj& p = *c.p;
+    const ProjOut& o = c.o;
+    const int r = p.r;
+    GemmProblem G;
+    memset(&G, 0, sizeof(G));
+    G.alpha = 1.0f;
+    G.bias = p.bias;
+    G.res = o.res; G.ldr = o.ldr;
+    G.y = o.y; G.ldy = o.ldy; G.y_f32 = o.y_f32;
+    G.geglu_F = o.geglu_F;
+    G.K0 = c.K; G.K1 = r;
+    if (!o.transposed) {
+        G.p0 = c.x; G.ldp0 = c.ldx; G.q0 = p.W; G.ldq0 = c.K;
+        G.p1 = r ? c.tbuf : nullptr; G.ldp1 = r; G.q1 = r ? p.B : nullptr; G.ldq1 = r;
+        G.Mp = c.M; G.N = c.N;
+    } else {
+        G.p0 = p.W; G.ldp0 = c.K; G.q0 = c.x; G.ldq0 = c.ldx;
+        G.p1 = r ? p.B : nullptr; G.ldp1 = r; G.q1 = r ? c.tbuf : nullptr; G.ldq1 = r;
+        G.Mp = c.N; G.N = c.M;
+        G.bias_on_rows = 1;
+    }
+    return push(g, G, stream);
+}
+
+static int flush(GemmGroup& g, hipStream_t stream) {
+    if (g.n == 0) return SD_OK;
+    int rc = launch_gemm_group(g, stream);
+    g.n = 0;
+    return rc;
+}
+
+// Run independent projections: every down-projection first (grouped launches), then every
+// base GEMM (grouped launches), so no base GEMM can read a down-projection still in flight.
+static int run_projections(const ProjCall* calls, int n, hipStream_t stream) {
+    GemmGroup g;
+    g.n = 0;
+    int rc;
+    for (int i = 0; i < n; ++i)
+        if (calls[i].M > 0 && (rc = push_down(g, stream, calls[i]))) return rc;
+    if ((rc = flush(g, stream))) return rc;
+    for (int i = 0; i < n; ++i)
+        if (calls[i].M > 0 && (rc = push_main(g, stream, calls[i]))) return rc;
+    return flush(g, stream);
+}
+
+static inline int pad8(int v) { return (v + 7) & ~7; }
+
+// ---------------------------------------------------------------------------------------
+// sub-layers (shared by the single-call entry points and the stack driver)
+// ---------------------------------------------------------------------------------------
+struct AttnWs { uint16_t *n, *q, *k, *vt, *a, *tq, *tk, *tv, *to; };
+
+static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, int rmax) {
+    const size_t M = (size_t)Bn * T, Mk = (size_t)Bn * Tk;
+    const size_t r = rmax > 0 ? rmax : 8;
+    w.n = (uint16_t*)ws.take(M * C * 2);
+    w.q = (uint16_t*)ws.take(M * C * 2);
+    w.k = (uint16_t*)ws.take(Mk * C * 2);
+    w.vt = (uint16_t*)ws.take((size_t)C * Bn * pad8(Tk) * 2);
+    w.a = (uint16_t*)ws.take(M * C * 2);
+    w.tq = (uint16_t*)ws.take(M * r * 2);
+    w.tk = (uint16_t*)ws.take(Mk * r * 2);
+    w.tv = (uint16_t*)ws.take(Mk * r * 2);
+    w.to = (uint16_t*)ws.take(M * r * 2);
+    return ws.ok();
+}
+
+static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx, int Tc, int Dc,
+                         const uint16_t* g, const uint16_t* b, float eps, const sd_proj& pq, const sd_proj& pk,
+                         const sd_proj& pv, const sd_proj& po, int Bn, int T, int C, int heads, const AttnWs& w,
+                         hipStream_t stream) {
+    const int M = Bn * T;
+    const int Tk = ctx ? Tc : T;
+    const int Kkv = ctx ? Dc : C;
+    const int Tkp = pad8(Tk);
+    int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
+    if (rc) return rc;
+    const uint16_t* src = ctx ? ctx : w.n;
+    // q, k, and v written transposed ([C, Bn * Tkp], one problem per sample so that each
+    // sample's keys start at a multiple of 8)
+    std::vector<ProjCall> calls;
+    calls.push_back({w.n, C, M, C, C, &pq, w.tq, {w.q, C, 0, nullptr, 0, false, 0}});
+    calls.push_back({src, Kkv, Bn * Tk, Kkv, C, &pk, w.tk, {w.k, C, 0, nullptr, 0, false, 0}});
+    for (int s = 0; s < Bn; ++s)
+        calls.push_back({src + (size_t)s * Tk * Kkv, Kkv, Tk, Kkv, C, &pv, w.tv + (size_t)s * Tk * (pv.r > 0 ? pv.r : 0),
+                         {w.vt + (size_t)s * Tkp, (int64_t)Bn * Tkp, 0, nullptr, 0, true, 0}});
+    if ((rc = run_projections(calls.data(), (int)calls.size(), stream))) return rc;
+    if ((rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, stream))) return rc;
+    ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
+    return run_projections(&oc, 1, stream);
+}
+
+struct FfWs { uint16_t *n, *g, *t1, *t2; };
+
+static bool carve_ff(Workspace& ws, FfWs& w, int M, int C, int F, int rmax) {
+    const size_t r = rmax > 0 ? rmax : 8;
+    w.n = (uint16_t*)ws.take((size_t)M * C * 2);
+    w.g = (uint16_t*)ws.take((size_t)M * F * 2);
+    w.t1 = (uint16_t*)ws.take((size_t)M * r * 2);
+    w.t2 = (uint16_t*)ws.take((size_t)M * r * 2);
+    return ws.ok();
+}
+
+static int ff_sublayer(const void* x, void* y, int io_f32, const uint16_t* g, const uint16_t* b, float eps,
+                       const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream) {
+    int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
+    if (rc) return rc;
+    ProjCall c1 = {w.n, C, M, C, F, &p1, w.t1, {w.g, F, 0, nullptr, 0, false, F}};
+    if ((rc = run_projections(&c1, 1, stream))) return rc;
+    ProjCall c2 = {w.g, F, M, F, C, &p2, w.t2, {y, C, io_f32, x, C, false, 0}};
+    return run_projections(&c2, 1, stream);
+}
+
+static int rmax_of(const sd_proj* const* ps, int n) {
+    int r = 0;
+    for (int i = 0; i < n; ++i)
+        if (ps[i] && ps[i]->r > r) r = ps[i]->r;
+    return r;
+}
+
+}  // namespace sd
+
+using namespace sd;
+
+extern "C" const char* sd_last_error(void) { return g_err; }
+extern "C" int32_t sd_version(void) { return 1; }
+
+// ---------------------------------------------------------------------------------------
+// lora_linear_fwd
+// ---------------------------------------------------------------------------------------
+extern "C" size_t sd_lora_linear_workspace_bytes(int32_t M, int32_t N, int32_t K, int32_t r, int32_t has_ln) {
+    (void)N;
+    if (M <= 0 || K <= 0) return 256;
+    Workspace ws(nullptr, 0);
+    size_t total = 0;
+    if (has_ln) total += round_up((size_t)M * K * 2, 256);
+    total += round_up((size_t)M * (r > 0 ? r : 8) * 2, 256);
+    (void)ws;
+    return total;
+}
+
+extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
+                                  const uint16_t* ln_beta, float ln_eps, const void* residual, void* y, int32_t y_dtype,
+                                  int32_t epilogue, int32_t M, int32_t N, int32_t K, void* ws, size_t ws_bytes, void* stream) {
+    SD_REQUIRE(M >= 0 && N >= 0, SD_EINVAL, "lora_linear: M=%d N=%d", M, N);
+    int rc = check_proj(p, "lora_linear", K);
+    if (rc) return rc;
+    SD_REQUIRE(x_dtype == SD_BF16 || x_dtype == SD_F32, SD_EINVAL, "lora_linear: x_dtype=%d", x_dtype);
+    SD_REQUIRE(y_dtype == SD_BF16 || y_dtype == SD_F32, SD_EINVAL, "lora_linear: y_dtype=%d", y_dtype);
+    SD_REQUIRE(epilogue == SD_EPI_NONE || epilogue == SD_EPI_GEGLU, SD_EINVAL, "lora_linear: epilogue=%d", epilogue);
+    const bool has_ln = ln_gamma || ln_beta;
+    SD_REQUIRE(!has_ln || (ln_gamma && ln_beta), SD_EINVAL, "lora_linear: LayerNorm needs both gamma and beta");
+    SD_REQUIRE(has_ln || x_dtype == SD_BF16, SD_EINVAL, "lora_linear: fp32 x is only accepted together with a LayerNorm");
+    SD_REQUIRE(!(epilogue == SD_EPI_GEGLU && residual), SD_EINVAL, "lora_linear: GEGLU epilogue takes no residual");
+    if (M == 0 || N == 0) return SD_OK;
+    SD_REQUIRE(x && y, SD_EINVAL, "lora_linear: x or y is null");
+    SD_REQUIRE(aligned16(x) && aligned16(y) && aligned16(residual) && aligned16(p->bias), SD_EINVAL,
+               "lora_linear: pointers must be 16-byte aligned");
+    SD_REQUIRE(ws_bytes >= sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln) && ws, SD_EWORKSPACE,
+               "lora_linear: workspace of %zu bytes, need %zu", ws_bytes, sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Workspace w(ws, ws_bytes);
+    const uint16_t* xin = static_cast<const uint16_t*>(x);
+    if (has_ln) {
+        uint16_t* n = (uint16_t*)w.take((size_t)M * K * 2);
+        if ((rc = launch_layernorm(x, x_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, n, M, K, s))) return rc;
+        xin = n;
+    }
+    uint16_t* t = (uint16_t*)w.take((size_t)M * (p->r > 0 ? p->r : 8) * 2);
+    SD_REQUIRE(w.ok(), SD_EWORKSPACE, "lora_linear: workspace too small");
+    ProjCall c = {xin, K, M, K, N, p, t, {y, N, y_dtype == SD_F32, residual, N, false, epilogue == SD_EPI_GEGLU ? N : 0}};
+    return run_projections(&c, 1, s);
+}
+
+// ---------------------------------------------------------------------------------------
+// attention_fwd / attn_block_fwd
+// ---------------------------------------------------------------------------------------
+extern "C" int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* vt, uint16_t* out, int32_t Bn,
+                                int32_t Tq, int32_t Tk, int32_t C, int32_t heads, void* stream) {
+    SD_REQUIRE(Bn >= 0 && Tq >= 0 && Tk >= 0 && heads > 0, SD_EINVAL, "attention: Bn=%d Tq=%d Tk=%d heads=%d", Bn, Tq, Tk, heads);
+    SD_REQUIRE(C == heads * 64, SD_EUNSUPPORTED, "attention: C=%d heads=%d (head dim must be 64)", C, heads);
+    if (Bn == 0 || Tq == 0) return SD_OK;
+    SD_REQUIRE(Tk >= 1, SD_EINVAL, "attention: no keys");
+    SD_REQUIRE(aligned16(q) && aligned16(k) && aligned16(vt) && aligned16(out), SD_EINVAL, "attention: pointers must be 16-byte aligned");
+    const int Tkp = pad8(Tk);
+    return launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max) {
+    (void)Dc;
+    if (Bn <= 0 || T <= 0 || C <= 0) return 256;
+    Workspace ws((void*)256, (size_t)-1 / 2);
+    AttnWs w;
+    carve_attn(ws, w, Bn, T, C, Tc > 0 ? (Tc > T ? Tc : T) : T, r_max);
+    return ws.used;
+}
+
+extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const uint16_t* ctx, int32_t Tc, int32_t Dc,
+                                 const uint16_t* ln_gamma, const uint16_t* ln_beta, float ln_eps, const sd_proj* q,
+                                 const sd_proj* k, const sd_proj* v, const sd_proj* o, int32_t Bn, int32_t T, int32_t C,
+                                 int32_t heads, void* ws, size_t ws_bytes, void* stream) {
+    SD_REQUIRE(Bn >= 0 && T >= 0 && C > 0 && heads > 0, SD_EINVAL, "attn_block: Bn=%d T=%d C=%d heads=%d", Bn, T, C, heads);
+    SD_REQUIRE(C == heads * 64, SD_EUNSUPPORTED, "attn_block: C=%d heads=%d (head dim must be 64)", C, heads);
+    SD_REQUIRE(io_dtype == SD_BF16 || io_dtype == SD_F32, SD_EINVAL, "attn_block: io_dtype=%d", io_dtype);
+    SD_REQUIRE(ln_gamma && ln_beta, SD_EINVAL, "attn_block: LayerNorm gamma/beta are null");
+    const int Kkv = ctx ? Dc : C;
+    if (ctx) SD_REQUIRE(Tc >= 1 && Dc > 0, SD_EINVAL, "attn_block: Tc=%d Dc=%d", Tc, Dc);
+    int rc;
+    if ((rc = check_proj(q, "attn_block q", C)) || (rc = check_proj(k, "attn_block k", Kkv)) ||
+        (rc = check_proj(v, "attn_block v", Kkv)) || (rc = check_proj(o, "attn_block o", C)))
+        return rc;
+    SD_REQUIRE(!v->bias, SD_EUNSUPPORTED, "attn_block: the v projection takes no bias");
+    if (Bn == 0 || T == 0) return SD_OK;
+    SD_REQUIRE(x && y && aligned16(x) && aligned16(y) && aligned16(ctx), SD_EINVAL, "attn_block: x/y/ctx null or misaligned");
+    const sd_proj* ps[4] = {q, k, v, o};
+    const int rmax = rmax_of(ps, 4);
+    const int Tk = ctx ? Tc : T;
+    Workspace w(ws, ws_bytes);
+    AttnWs aw;
+    SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax), SD_EWORKSPACE, "attn_block: workspace of %zu bytes is too small", ws_bytes);
+    return attn_sublayer(x, y, io_dtype == SD_F32, ctx, Tc, Dc, ln_gamma, ln_beta, ln_eps, *q, *k, *v, *o, Bn, T, C, heads, aw,
+                         static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------
+// ff_block_fwd
+// ---------------------------------------------------------------------------------------
+extern "C" size_t sd_ff_block_workspace_bytes(int32_t M, int32_t C, int32_t F, int32_t r_max) {
+    if (M <= 0 || C <= 0 || F <= 0) return 256;
+    Workspace ws((void*)256, (size_t)-1 / 2);
+    FfWs w;
+    carve_ff(ws, w, M, C, F, r_max);
+    return ws.used;
+}
+
+extern "C" int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype, const uint16_t* ln_gamma, const uint16_t* ln_beta,
+                               float ln_eps, const sd_proj* ff1, const sd_proj* ff2, int32_t M, int32_t C, int32_t F, void* ws,
+                               size_t ws_bytes, void* stream) {
+    SD_REQUIRE(M >= 0 && C > 0 && F > 0, SD_EINVAL, "ff_block: M=%d C=%d F=%d", M, C, F);
+    SD_REQUIRE(io_dtype == SD_BF16 || io_dtype == SD_F32, SD_EINVAL, "ff_block: io_dtype=%d", io_dtype);
+    SD_REQUIRE(ln_gamma && ln_beta, SD_EINVAL, "ff_block: LayerNorm gamma/beta are null");
+    int rc;
+    if ((rc = check_proj(ff1, "ff_block ff1", C)) || (rc = check_proj(ff2, "ff_block ff2", F))) return rc;
+    if (M == 0) return SD_OK;
+    SD_REQUIRE(x && y && aligned16(x) && aligned16(y), SD_EINVAL, "ff_block: x/y null or misaligned");
+    const sd_proj* ps[2] = {ff1, ff2};
+    Workspace w(ws, ws_bytes);
+    FfWs fw;
+    SD_REQUIRE(ws && carve_ff(w, fw, M, C, F, rmax_of(ps, 2)), SD_EWORKSPACE, "ff_block: workspace of %zu bytes is too small", ws_bytes);
+    return ff_sublayer(x, y, io_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, *ff1, *ff2, M, C, F, fw, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------
+// groupnorm_fwd
+// ---------------------------------------------------------------------------------------
+extern "C" size_t sd_groupnorm_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t groups) {
+    (void)C;
+    if (Bn <= 0 || T <= 0 || groups <= 0) return 256;
+    return round_up(groupnorm_partials_bytes(Bn, T, groups), 256);
+}
+
+extern "C" int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta, int32_t Bn,
+                                int32_t T, int32_t C, int32_t groups, float eps, void* ws, size_t ws_bytes, void* stream) {
+    SD_REQUIRE(Bn >= 0 && T >= 0 && C > 0 && groups > 0, SD_EINVAL, "groupnorm: Bn=%d T=%d C=%d groups=%d", Bn, T, C, groups);
+    if (Bn == 0 || T == 0) return SD_OK;
+    SD_REQUIRE(x && y && gamma && beta, SD_EINVAL, "groupnorm: null pointer");
+    SD_REQUIRE(aligned16(x) && aligned16(y) && aligned16(gamma) && aligned16(beta), SD_EINVAL, "groupnorm: misaligned pointer");
+    SD_REQUIRE(ws && ws_bytes >= sd_groupnorm_workspace_bytes(Bn, T, C, groups), SD_EWORKSPACE, "groupnorm: workspace of %zu bytes, need %zu",
+               ws_bytes, sd_groupnorm_workspace_bytes(Bn, T, C, groups));
+    return launch_groupnorm(x, y, gamma, beta, Bn, T, C, groups, eps, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------------------
+// spatial_transformer_fwd
+// ---------------------------------------------------------------------------------------
+namespace sd {
+struct StackWs { float* h; uint16_t* g; float* gn; AttnWs a; FfWs f; };
+static bool carve_stack(Workspace& ws, StackWs& w, int Bn, int T, int C, int Tc, int rmax) {
+    const size_t M = (size_t)Bn * T;
+    w.h = (float*)ws.take(M * C * 4);
+    w.g = (uint16_t*)ws.take(M * C * 2);
+    w.gn = (float*)ws.take(groupnorm_partials_bytes(Bn, T, 32));
+    carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax);
+    carve_ff(ws, w.f, (int)M, C, 4 * C, rmax);
+    return ws.ok();
+}
+}  // namespace sd
+
+extern "C" size_t sd_spatial_transformer_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max) {
+    (void)Dc;
+    if (Bn <= 0 || T <= 0 || C <= 0) return 256;
+    Workspace ws((void*)256, (size_t)-1 / 2);
+    StackWs w;
+    carve_stack(ws, w, Bn, T, C, Tc, r_max);
+    return ws.used;
+}
+
+extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx, const sd_stack_params* p, uint16_t* y,
+                                          int32_t Bn, int32_t T, int32_t C, int32_t heads, int32_t Tc, int32_t Dc, void* ws,
+                                          size_t ws_bytes, void* stream) {
+    SD_REQUIRE(Bn >= 0 && T >= 0 && C > 0 && heads > 0 && Tc >= 1 && Dc > 0, SD_EINVAL,
+               "spatial_transformer: Bn=%d T=%d C=%d heads=%d Tc=%d Dc=%d", Bn, T, C, heads, Tc, Dc);
+    SD_REQUIRE(C == heads * 64, SD_EUNSUPPORTED, "spatial_transformer: C=%d heads=%d (head dim must be 64)", C, heads);
+    SD_REQUIRE(C % 32 == 0 && (C / 32) % 2 == 0, SD_EUNSUPPORTED, "spatial_transformer: C=%d does not split into 32 even groups", C);
+    SD_REQUIRE(p && p->depth >= 0 && (p->depth == 0 || p->blocks), SD_EINVAL, "spatial_transformer: params null or depth < 0");
+    SD_REQUIRE(p->gn_g && p->gn_b, SD_EINVAL, "spatial_transformer: GroupNorm affine is null");
+    int rc;
+    if ((rc = check_proj(&p->proj_in, "proj_in", C)) || (rc = check_proj(&p->proj_out, "proj_out", C))) return rc;
+    int rmax = 0;
+    for (int i = 0; i < p->depth; ++i) {
+        const sd_block_params& b = p->blocks[i];
+        SD_REQUIRE(b.ln1_g && b.ln1_b && b.ln2_g && b.ln2_b && b.ln3_g && b.ln3_b, SD_EINVAL, "block %d: LayerNorm affine is null", i);
+        if ((rc = check_proj(&b.q1, "q1", C)) || (rc = check_proj(&b.k1, "k1", C)) || (rc = check_proj(&b.v1, "v1", C)) ||
+            (rc = check_proj(&b.o1, "o1", C)) || (rc = check_proj(&b.q2, "q2", C)) || (rc = check_proj(&b.k2, "k2", Dc)) ||
+            (rc = check_proj(&b.v2, "v2", Dc)) || (rc = check_proj(&b.o2, "o2", C)) || (rc = check_proj(&b.ff1, "ff1", C)) ||
+            (rc = check_proj(&b.ff2, "ff2", 4 * C)))
+            return rc;
+        SD_REQUIRE(!b.v1.bias && !b.v2.bias, SD_EUNSUPPORTED, "block %d: v projections take no bias", i);
+        const sd_proj* ps[10] = {&b.q1, &b.k1, &b.v1, &b.o1, &b.q2, &b.k2, &b.v2, &b.o2, &b.ff1, &b.ff2};
+        const int r = rmax_of(ps, 10);
+        if (r > rmax) rmax = r;
+    }
+    if (Bn == 0 || T == 0) return SD_OK;
+    SD_REQUIRE(x && y && ctx && aligned16(x) && aligned16(y) && aligned16(ctx), SD_EINVAL, "spatial_transformer: x/y/ctx null or misaligned");
+    Workspace w(ws, ws_bytes);
+    StackWs sw;
+    SD_REQUIRE(ws && carve_stack(w, sw, Bn, T, C, Tc, rmax), SD_EWORKSPACE, "spatial_transformer: workspace of %zu bytes, need %zu", ws_bytes,
+               sd_spatial_transformer_workspace_bytes(Bn, T, C, Tc, Dc, rmax));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int M = Bn * T;
+    // GroupNorm -> proj_in -> fp32 residual stream h
+    if ((rc = launch_groupnorm(x, sw.g, p->gn_g, p->gn_b, Bn, T, C, 32, 1e-6f, sw.gn, s))) return rc;
+    ProjCall cin = {sw.g, C, M, C, C, &p->proj_in, sw.f.t1, {sw.h, C, 1, nullptr, 0, false, 0}};
+    if ((rc = run_projections(&cin, 1, s))) return rc;
+    for (int i = 0; i < p->depth; ++i) {
+        const sd_block_params& b = p->blocks[i];
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, nullptr, 0, 0, b.ln1_g, b.ln1_b, 1e-5f, b.q1, b.k1, b.v1, b.o1, Bn, T, C, heads, sw.a, s))) return rc;
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s))) return rc;
+        if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s))) return rc;
+    }
+    // proj_out + input residual, bf16 out
+    if ((rc = launch_cvt_f32_to_bf16(sw.h, sw.g, (size_t)M * C, s))) return rc;
+    ProjCall cout = {sw.g, C, M, C, C, &p->proj_out, sw.f.t1, {y, C, 0, x, C, false, 0}};
+    return run_projections(&cout, 1, s);
+}
+
+// ---------------------------------------------------------------------------------------
+// multi_lora_linear_fwd
+// ---------------------------------------------------------------------------------------
+extern "C" size_t sd_multi_lora_linear_workspace_bytes(int32_t M, int32_t r_max) {
+    if (M <= 0) return 256;
+    return round_up((size_t)M * (r_max > 0 ? r_max : 8) * 2, 256);
+}
+
+extern "C" int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, const uint16_t* bias, const uint16_t* const* A_ptrs,
+                                        const uint16_t* const* B_ptrs, const int32_t* ranks, const float* scales,
+                                        const int32_t* seg_offsets, const int32_t* seg_adapter, int32_t nseg, int32_t nadapters,
+                                        uint16_t* y, int32_t M, int32_t N, int32_t K, void* ws, size_t ws_bytes, void* stream) {
+    SD_REQUIRE(M >= 0 && N >= 0 && K > 0 && K % 8 == 0, SD_EINVAL, "multi_lora: M=%d N=%d K=%d", M, N, K);
+    SD_REQUIRE(nseg >= 0 && nadapters >= 0, SD_EINVAL, "multi_lora: nseg=%d nadapters=%d", nseg, nadapters);
+    if (M == 0 || N == 0) return SD_OK;
+    SD_REQUIRE(x && W && y && aligned16(x) && aligned16(W) && aligned16(y) && aligned16(bias), SD_EINVAL, "multi_lora: x/W/y null or misaligned");
+    SD_REQUIRE(seg_offsets && seg_adapter && nseg >= 1, SD_EINVAL, "multi_lora: segment table missing");
+    SD_REQUIRE(nadapters == 0 || (A_ptrs && B_ptrs && ranks && scales), SD_EINVAL, "multi_lora: adapter tables missing");
+    SD_REQUIRE(seg_offsets[0] == 0 && seg_offsets[nseg] == M, SD_EINVAL, "multi_lora: segments must cover [0, M)");
+    int rmax = 0;
+    for (int a = 0; a < nadapters; ++a) {
+        SD_REQUIRE(ranks[a] > 0 && ranks[a] % 8 == 0, SD_EUNSUPPORTED, "multi_lora: adapter %d rank %d is not a positive multiple of 8", a, ranks[a]);
+        SD_REQUIRE(A_ptrs[a] && B_ptrs[a] && aligned16(A_ptrs[a]) && aligned16(B_ptrs[a]), SD_EINVAL, "multi_lora: adapter %d A/B null or misaligned", a);
+        if (ranks[a] > rmax) rmax = ranks[a];
+    }
+    for (int i = 0; i < nseg; ++i) {
+        SD_REQUIRE(seg_offsets[i + 1] >= seg_offsets[i], SD_EINVAL, "multi_lora: segment %d has negative length", i);
+        SD_REQUIRE(seg_adapter[i] >= -1 && seg_adapter[i] < nadapters, SD_EINVAL, "multi_lora: segment %d names adapter %d", i, seg_adapter[i]);
+    }
+    SD_REQUIRE(ws && ws_bytes >= sd_multi_lora_linear_workspace_bytes(M, rmax), SD_EWORKSPACE, "multi_lora: workspace of %zu bytes, need %zu",
+               ws_bytes, sd_multi_lora_linear_workspace_bytes(M, rmax));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint16_t* t = static_cast<uint16_t*>(ws);   // segment i's down-projection lives at t + offset_i * rmax
+    std::vector<sd_proj> projs(nseg);
+    std::vector<ProjCall> calls;
+    for (int i = 0; i < nseg; ++i) {
+        const int lo = seg_offsets[i], rows = seg_offsets[i + 1] - lo;
+        if (rows == 0) continue;
+        const int a = seg_adapter[i];
+        sd_proj& pr = projs[i];
+        pr.W = W; pr.bias = bias; pr.A = a >= 0 ? A_ptrs[a] : nullptr; pr.B = a >= 0 ? B_ptrs[a] : nullptr;
+        pr.r = a >= 0 ? ranks[a] : 0; pr.scale = a >= 0 ? scales[a] : 0.f;
+        calls.push_back({x + (size_t)lo * K, K, rows, K, N, &pr, t + (size_t)lo * rmax, {y + (size_t)lo * N, N, 0, nullptr, 0, false, 0}});
+    }
+    return run_projections(calls.data(), (int)calls.size(), s);
+}

@@ -1,0 +1,240 @@
+// Flash-style attention for gfx950, head dim 64, no mask: softmax(q k^T / 8) v per
+// (sample, head) without ever writing the scores (the transformer block's self-attention
+// over the latent tokens and cross-attention to the text tokens).
+//
+// The kernel works on the TRANSPOSED score tile S^T = K Q^T: with the 32x32x16 bf16 MFMA
+// the accumulator of lane l then holds one query (column l % 32) and 16 of the tile's keys
+// (rows), so the softmax row maximum and row sum are in-register reductions plus a single
+// exchange between the two half-wavefronts, the running rescale factor is a per-lane
+// scalar, and the exponentials, packed to bf16, are already laid out as the B operand of
+// the second MFMA, O^T += V^T P^T.  V is consumed transposed ([C, keys]), which is how the
+// v-projection GEMM writes it, so both K and V^T tiles are staged with 16-byte rows.
+//
+// Workgroup: 4 wavefronts, each owning 32*QB queries; K / V^T tiles of 64 keys are staged
+// in LDS (XOR-swizzled 16-byte chunks), double-buffered against the global loads.
+#include "common.hpp"
+
+namespace sd {
+
+__device__ __forceinline__ int aswz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+
+template <int QB>
+__global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
+                                                        const uint16_t* __restrict__ k, int64_t ldk,
+                                                        const uint16_t* __restrict__ vt, int64_t ldvt,
+                                                        uint16_t* __restrict__ out, int64_t ldo,
+                                                        int Tq, int Tk, int Tkp, float c) {
+    constexpr int BQ = 4 * 32 * QB;
+    __shared__ u32x4 ldsK[2][64 * 8];   // [key][8 chunks of 8 d]
+    __shared__ u32x4 ldsV[2][64 * 8];   // [d][8 chunks of 8 keys]
+
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int q0 = blockIdx.x * BQ + wave * 32 * QB;
+
+    // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[row l32][d = kk*16 + hi*8 ..+8]
+    bf16x8 qf[QB][4];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        int row = q0 + qb * 32 + l32;
+        row = row < Tq ? row : Tq - 1;
+        const uint16_t* qp = q + ((int64_t)b * Tq + row) * ldq + head * 64 + hi * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + kk * 16));
+    }
+
+    // ---- tile loaders: thread owns chunks (row lrow, lrow + 32; chunk lc) of both tiles
+    const int lrow = tid >> 3, lc = tid & 7;
+    const uint16_t* kbase = k + (int64_t)b * Tk * ldk + head * 64 + lc * 8;
+    const uint16_t* vbase = vt + (int64_t)(head * 64) * ldvt + (int64_t)b * Tkp + lc * 8;
+    u32x4 rk[2], rv[2];
+    auto load_kv = [&](int t) {
+        const int key0 = t * 64;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = lrow + i * 32;
+            int key = key0 + r;
+            key = key < Tk ? key : Tk - 1;
+            rk[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * ldk);
+            const int kc = key0 + lc * 8;   // first key of this V^T chunk
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (kc < Tkp) {
+                v = *reinterpret_cast<const u32x4*>(vbase + (int64_t)r * ldvt + key0);
+                if (kc + 8 > Tk) {   // zero the padding keys: 0 * garbage must stay 0
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        uint32_t w = v[e];
+                        if (kc + 2 * e >= Tk) w &= 0xffff0000u;
+                        if (kc + 2 * e + 1 >= Tk) w &= 0x0000ffffu;
+                        v[e] = w;
+                    }
+                }
+            }
+            rv[i] = v;
+        }
+    };
+    auto store_kv = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int r = lrow + i * 32;
+            ldsK[buf][r * 8 + aswz(r, lc)] = rk[i];
+            ldsV[buf][r * 8 + aswz(r, lc)] = rv[i];
+        }
+    };
+
+    f32x16 o[QB][2];
+    float m[QB], l[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        m[qb] = -INFINITY;
+        l[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[qb][db][v] = 0.f;
+    }
+
+    const int nt = (Tk + 63) >> 6;
+    load_kv(0);
+    store_kv(0);
+    __syncthreads();
+
+#pragma unroll 1
+    for (int t = 0; t < nt; ++t) {
+        const bool more = t + 1 < nt;
+        if (more) load_kv(t + 1);
+        const u32x4* lk = ldsK[t & 1];
+        const u32x2* lv = reinterpret_cast<const u32x2*>(ldsV[t & 1]);
+
+        // ---- S^T tile: 64 keys x (32*QB) queries
+        f32x16 s[QB][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[qb][kb][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int r = kb * 32 + l32;
+                const bf16x8 a = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, kk * 2 + hi)]);
+#pragma unroll
+                for (int qb = 0; qb < QB; ++qb)
+                    s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], s[qb][kb], 0, 0, 0);
+            }
+        // mask the keys past Tk (last tile only)
+        if (t * 64 + 64 > Tk) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                    if (key >= Tk) {
+#pragma unroll
+                        for (int qb = 0; qb < QB; ++qb) s[qb][kb][v] = -INFINITY;
+                    }
+                }
+        }
+
+        // ---- online softmax; this lane's query is column l32, its keys are its registers
+        bf16x8 pf[QB][2][2];
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            float mx = s[qb][0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kb][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float mnew = fmaxf(m[qb], mx);
+            const float alpha = __builtin_amdgcn_exp2f((m[qb] - mnew) * c);
+            m[qb] = mnew;
+            const float mc = mnew * c;
+            float ls = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int g2 = 0; g2 < 2; ++g2) {
+                    u32x4 pk;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float p0 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e] * c - mc);
+                        const float p1 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e + 1] * c - mc);
+                        ls += p0 + p1;
+                        pk[e] = pack_bf16x2(p0, p1);
+                    }
+                    pf[qb][kb][g2] = __builtin_bit_cast(bf16x8, pk);
+                }
+            l[qb] = l[qb] * alpha + ls;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[qb][db][v] *= alpha;
+        }
+
+        // ---- O^T += V^T P^T.  k-slot j of sub-step (kb, g2) is key kb*32 + 16*g2 + 8*(j/4) + 4*hi + j%4
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+                for (int db = 0; db < 2; ++db) {
+                    const int r = db * 32 + l32;
+                    const int ch = kb * 4 + g2 * 2;
+                    const u32x2 lo = lv[(r * 8 + aswz(r, ch)) * 2 + hi];
+                    const u32x2 hh = lv[(r * 8 + aswz(r, ch + 1)) * 2 + hi];
+                    const u32x4 av = {lo[0], lo[1], hh[0], hh[1]};
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+                    for (int qb = 0; qb < QB; ++qb)
+                        o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][kb][g2], o[qb][db], 0, 0, 0);
+                }
+
+        if (more) store_kv((t + 1) & 1);
+        __syncthreads();
+    }
+
+    // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+        const float lt = l[qb] + __shfl_xor(l[qb], 32, 64);
+        const float inv = 1.0f / lt;
+        const int row = q0 + qb * 32 + l32;
+        if (row < Tq) {
+            uint16_t* op = out + ((int64_t)b * Tq + row) * ldo + head * 64 + 4 * hi;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    u32x2 w;
+                    w[0] = pack_bf16x2(o[qb][db][4 * v4] * inv, o[qb][db][4 * v4 + 1] * inv);
+                    w[1] = pack_bf16x2(o[qb][db][4 * v4 + 2] * inv, o[qb][db][4 * v4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(op + db * 32 + 8 * v4) = w;
+                }
+        }
+    }
+}
+
+int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
+                     const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
+                     int Bn, int Tq, int Tk, int Tkp, int heads, hipStream_t stream) {
+    SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
+    SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
+    SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
+    if (Bn <= 0 || Tq <= 0 || heads <= 0) return SD_OK;
+    const float c = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
+    if (Tq >= 2048) {
+        dim3 grid((Tq + 255) / 256, heads, Bn);
+        hipLaunchKernelGGL(attention_kernel<2>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, c);
+    } else {
+        dim3 grid((Tq + 127) / 128, heads, Bn);
+        hipLaunchKernelGGL(attention_kernel<1>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, c);
+    }
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+}  // namespace sd

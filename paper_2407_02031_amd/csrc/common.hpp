@@ -1,0 +1,108 @@
+// Shared device/host helpers of the gfx950 kernels: vector types, bf16 conversion,
+// error reporting.  gfx950 only; wavefront = 64 lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "../../include/swiftdiff.h"
+
+namespace sd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// ---- bf16 <-> f32 (bit level; round-to-nearest-even) ----
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);   // finite inputs only on this path
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// ---- error text (per host thread) ----
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define SD_HIP_CHECK(expr)                                         \
+    do {                                                           \
+        hipError_t _e = (expr);                                    \
+        if (_e != hipSuccess) return ::sd::hip_fail(_e, #expr);    \
+    } while (0)
+
+#define SD_REQUIRE(cond, code, ...)                                \
+    do {                                                           \
+        if (!(cond)) { ::sd::set_error(__VA_ARGS__); return (code); } \
+    } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Bump allocator over the caller's workspace (256-byte granules).
+struct Workspace {
+    char* base; size_t size; size_t used;
+    Workspace(void* p, size_t n) : base(static_cast<char*>(p)), size(n), used(0) {}
+    void* take(size_t bytes) {
+        size_t b = round_up(bytes, 256);
+        if (!base || used + b > size) { used = size + 1; return nullptr; }
+        void* r = base + used; used += b; return r;
+    }
+    bool ok() const { return used <= size; }
+};
+
+// ---------------------------------------------------------------------------------------
+// Grouped GEMM:  D[p][q] = alpha * sum_k P[p][k] Q[q][k]  over two K segments, then
+// + bias, GEGLU, + residual, store.  Both operands are K-contiguous (row-major [rows, K]).
+// ---------------------------------------------------------------------------------------
+struct GemmProblem {
+    const uint16_t* p0; const uint16_t* q0;   // segment 0: P [Mp, K0], Q [Nq, K0]
+    const uint16_t* p1; const uint16_t* q1;   // segment 1 (LoRA: P = scaled x A^T, Q = B), or null
+    const uint16_t* bias;                      // per output column (or per row if bias_on_rows)
+    const void* res;                           // [Mp, N] of the output dtype, or null
+    void* y;
+    int64_t ldp0, ldq0, ldp1, ldq1, ldr, ldy;
+    int32_t Mp, N;                             // output rows, output columns
+    int32_t K0, K1;
+    int32_t geglu_F;                           // > 0: Q has 2F rows (value, gate); N == F
+    int32_t y_f32;                             // output/residual dtype: 1 fp32, 0 bf16
+    int32_t bias_on_rows;
+    float alpha;
+    int32_t tile_begin, tiles_m, tiles_n;      // filled by the launcher
+};
+
+constexpr int GEMM_MAX_PROBLEMS = 16;
+struct GemmGroup {
+    int32_t n;
+    int32_t total_tiles;
+    GemmProblem p[GEMM_MAX_PROBLEMS];
+};
+
+// Launch every problem of `g` in one grid.  Problems must all be GEGLU or all plain.
+int launch_gemm_group(GemmGroup& g, hipStream_t stream);
+
+// LayerNorm rows of x [M, C] (fp32 or bf16) -> bf16.
+int launch_layernorm(const void* x, int x_f32, const uint16_t* gamma, const uint16_t* beta, float eps,
+                     uint16_t* y, int M, int C, hipStream_t stream);
+// fp32 [n] -> bf16, bf16 -> fp32 converters for the stack boundary
+int launch_cvt_bf16_to_f32(const uint16_t* x, float* y, size_t n, hipStream_t stream);
+int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t stream);
+
+int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
+                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream);
+size_t groupnorm_partials_bytes(int Bn, int T, int groups);
+
+int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
+                     const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
+                     int Bn, int Tq, int Tk, int Tkp, int heads, hipStream_t stream);
+
+}  // namespace sd

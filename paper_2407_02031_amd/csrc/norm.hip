@@ -1,0 +1,231 @@
+// LayerNorm (per token) and token-major GroupNorm(32) for gfx950, plus the dtype
+// converters at the stack boundary.  All statistics in fp32, biased variance, two passes
+// over register-resident (LayerNorm) or shift-centred (GroupNorm) data.  HBM-bound.
+#include "common.hpp"
+
+namespace sd {
+
+// ---------------------------------------------------------------------------------------
+// LayerNorm: one wavefront per row, the row lives in registers (C <= 2048, C % 4 == 0).
+// ---------------------------------------------------------------------------------------
+constexpr int LN_MAXJ = 8;   // float4 chunks per lane: 64 lanes * 4 * 8 = 2048 channels
+
+template <bool XF32>
+__global__ __launch_bounds__(256) void layernorm_kernel(const void* __restrict__ xv, const uint16_t* __restrict__ gamma,
+                                                        const uint16_t* __restrict__ beta, float eps,
+                                                        uint16_t* __restrict__ y, int M, int C) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int nch = C >> 2;   // 4-element chunks per row
+    float v[LN_MAXJ][4];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int ch = lane + j * 64;
+        if (ch < nch) {
+            if (XF32) {
+                const float4 t = reinterpret_cast<const float4*>(static_cast<const float*>(xv) + (size_t)row * C)[ch];
+                v[j][0] = t.x; v[j][1] = t.y; v[j][2] = t.z; v[j][3] = t.w;
+            } else {
+                const uint2 t = reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(xv) + (size_t)row * C)[ch];
+                v[j][0] = bf16lo_to_f32(t.x); v[j][1] = bf16hi_to_f32(t.x);
+                v[j][2] = bf16lo_to_f32(t.y); v[j][3] = bf16hi_to_f32(t.y);
+            }
+            s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+        } else {
+            v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.f;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    const float mean = s / (float)C;
+    float s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int ch = lane + j * 64;
+        if (ch < nch) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[j][e] -= mean; s2 += v[j][e] * v[j][e]; }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) s2 += __shfl_xor(s2, o, 64);
+    const float rstd = rsqrtf(s2 / (float)C + eps);
+#pragma unroll
+    for (int j = 0; j < LN_MAXJ; ++j) {
+        const int ch = lane + j * 64;
+        if (ch < nch) {
+            const uint2 gg = reinterpret_cast<const uint2*>(gamma)[ch];
+            const uint2 bb = reinterpret_cast<const uint2*>(beta)[ch];
+            const float o0 = v[j][0] * rstd * bf16lo_to_f32(gg.x) + bf16lo_to_f32(bb.x);
+            const float o1 = v[j][1] * rstd * bf16hi_to_f32(gg.x) + bf16hi_to_f32(bb.x);
+            const float o2 = v[j][2] * rstd * bf16lo_to_f32(gg.y) + bf16lo_to_f32(bb.y);
+            const float o3 = v[j][3] * rstd * bf16hi_to_f32(gg.y) + bf16hi_to_f32(bb.y);
+            uint2 o;
+            o.x = pack_bf16x2(o0, o1);
+            o.y = pack_bf16x2(o2, o3);
+            reinterpret_cast<uint2*>(y + (size_t)row * C)[ch] = o;
+        }
+    }
+}
+
+int launch_layernorm(const void* x, int x_f32, const uint16_t* gamma, const uint16_t* beta, float eps,
+                     uint16_t* y, int M, int C, hipStream_t stream) {
+    SD_REQUIRE(C % 4 == 0 && C > 0 && C <= 64 * 4 * LN_MAXJ, SD_EUNSUPPORTED, "layernorm: C=%d (need C %% 4 == 0, C <= %d)", C,
+               64 * 4 * LN_MAXJ);
+    if (M <= 0) return SD_OK;
+    dim3 grid((M + 3) / 4), block(256);
+    if (x_f32) hipLaunchKernelGGL(layernorm_kernel<true>, grid, block, 0, stream, x, gamma, beta, eps, y, M, C);
+    else hipLaunchKernelGGL(layernorm_kernel<false>, grid, block, 0, stream, x, gamma, beta, eps, y, M, C);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// dtype converters (n % 4 == 0 handled by the tail loop)
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cvt_bf16_f32_kernel(const uint16_t* __restrict__ x, float* __restrict__ y, size_t n) {
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i + 3 < n) {
+        const uint2 t = *reinterpret_cast<const uint2*>(x + i);
+        float4 o = {bf16lo_to_f32(t.x), bf16hi_to_f32(t.x), bf16lo_to_f32(t.y), bf16hi_to_f32(t.y)};
+        *reinterpret_cast<float4*>(y + i) = o;
+    } else {
+        for (; i < n; ++i) y[i] = bf16_to_f32(x[i]);
+    }
+}
+__global__ __launch_bounds__(256) void cvt_f32_bf16_kernel(const float* __restrict__ x, uint16_t* __restrict__ y, size_t n) {
+    size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i + 3 < n) {
+        const float4 t = *reinterpret_cast<const float4*>(x + i);
+        uint2 o;
+        o.x = pack_bf16x2(t.x, t.y);
+        o.y = pack_bf16x2(t.z, t.w);
+        *reinterpret_cast<uint2*>(y + i) = o;
+    } else {
+        for (; i < n; ++i) y[i] = (uint16_t)f32_to_bf16_bits(x[i]);
+    }
+}
+int launch_cvt_bf16_to_f32(const uint16_t* x, float* y, size_t n, hipStream_t stream) {
+    if (!n) return SD_OK;
+    hipLaunchKernelGGL(cvt_bf16_f32_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, x, y, n);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t stream) {
+    if (!n) return SD_OK;
+    hipLaunchKernelGGL(cvt_f32_bf16_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, stream, x, y, n);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// GroupNorm, token-major [Bn, T, C].  Pass 1: per (sample, token chunk, group) sums of
+// (x - shift) and (x - shift)^2 with shift = the group's first element in the sample
+// (shifted-data variance: no catastrophic cancellation for data with a large mean).
+// Pass 2: combine the chunk partials in a fixed order and normalise.
+// Thread t of a block owns channel pair (2t, 2t+1); groups hold an even number of channels.
+// ---------------------------------------------------------------------------------------
+constexpr int GN_TCHUNK = 32;   // tokens per block
+
+__global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* __restrict__ partials,
+                                         int T, int C, int groups, int nchunks) {
+    extern __shared__ float sh[];   // [C/2][2]
+    const int b = blockIdx.y, chunk = blockIdx.x;
+    const int cp = threadIdx.x;
+    const int cpg = C / groups;
+    const int npairs = C >> 1;
+    const uint16_t* xb = x + (size_t)b * T * C;
+    const int t0 = chunk * GN_TCHUNK;
+    const int t1 = min(T, t0 + GN_TCHUNK);
+    float s1 = 0.f, s2 = 0.f;
+    if (cp < npairs) {
+        const int g = (2 * cp) / cpg;
+        const float shift = bf16_to_f32(xb[g * cpg]);
+        for (int t = t0; t < t1; ++t) {
+            const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
+            const float a = bf16lo_to_f32(pr) - shift, c = bf16hi_to_f32(pr) - shift;
+            s1 += a + c;
+            s2 += a * a + c * c;
+        }
+        sh[2 * cp] = s1;
+        sh[2 * cp + 1] = s2;
+    }
+    __syncthreads();
+    if (cp < groups) {
+        const int ppg = cpg >> 1;
+        float a1 = 0.f, a2 = 0.f;
+        for (int i = 0; i < ppg; ++i) { a1 += sh[2 * (cp * ppg + i)]; a2 += sh[2 * (cp * ppg + i) + 1]; }
+        float* o = partials + (((size_t)b * nchunks + chunk) * groups + cp) * 2;
+        o[0] = a1;
+        o[1] = a2;
+    }
+}
+
+__global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
+                                       const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ beta,
+                                       const float* __restrict__ partials, int T, int C, int groups, int nchunks, float eps) {
+    extern __shared__ float sh[];   // [groups][2]: mean, rstd
+    const int b = blockIdx.y, chunk = blockIdx.x;
+    const int cp = threadIdx.x;
+    const int cpg = C / groups;
+    const int npairs = C >> 1;
+    const uint16_t* xb = x + (size_t)b * T * C;
+    uint16_t* yb = y + (size_t)b * T * C;
+    if (cp < groups) {
+        float a1 = 0.f, a2 = 0.f;
+        for (int c = 0; c < nchunks; ++c) {
+            const float* p = partials + (((size_t)b * nchunks + c) * groups + cp) * 2;
+            a1 += p[0];
+            a2 += p[1];
+        }
+        const float n = (float)T * (float)cpg;
+        const float m1 = a1 / n;
+        const float var = fmaxf(a2 / n - m1 * m1, 0.f);
+        sh[2 * cp] = bf16_to_f32(xb[cp * cpg]) + m1;
+        sh[2 * cp + 1] = rsqrtf(var + eps);
+    }
+    __syncthreads();
+    if (cp >= npairs) return;
+    const int g = (2 * cp) / cpg;
+    const float mean = sh[2 * g], rstd = sh[2 * g + 1];
+    const uint32_t gg = reinterpret_cast<const uint32_t*>(gamma)[cp];
+    const uint32_t bb = reinterpret_cast<const uint32_t*>(beta)[cp];
+    const float g0 = bf16lo_to_f32(gg) * rstd, g1 = bf16hi_to_f32(gg) * rstd;
+    const float b0 = bf16lo_to_f32(bb), b1 = bf16hi_to_f32(bb);
+    const int t0 = chunk * GN_TCHUNK;
+    const int t1 = min(T, t0 + GN_TCHUNK);
+    for (int t = t0; t < t1; ++t) {
+        const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
+        const float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
+        const float o1 = (bf16hi_to_f32(pr) - mean) * g1 + b1;
+        reinterpret_cast<uint32_t*>(yb + (size_t)t * C)[cp] = pack_bf16x2(o0, o1);
+    }
+}
+
+size_t groupnorm_partials_bytes(int Bn, int T, int groups) {
+    const size_t nchunks = (size_t)(T + GN_TCHUNK - 1) / GN_TCHUNK;
+    return (size_t)Bn * nchunks * groups * 2 * sizeof(float);
+}
+
+int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
+                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream) {
+    SD_REQUIRE(groups > 0 && C % groups == 0 && (C / groups) % 2 == 0, SD_EUNSUPPORTED,
+               "groupnorm: C=%d groups=%d (need an even number of channels per group)", C, groups);
+    SD_REQUIRE(C <= 2048, SD_EUNSUPPORTED, "groupnorm: C=%d > 2048", C);
+    if (Bn <= 0 || T <= 0) return SD_OK;
+    const int nchunks = (T + GN_TCHUNK - 1) / GN_TCHUNK;
+    int threads = ((C / 2 + 63) / 64) * 64;
+    if (threads < 64) threads = 64;
+    if (threads < groups) threads = ((groups + 63) / 64) * 64;
+    dim3 grid(nchunks, Bn);
+    hipLaunchKernelGGL(groupnorm_partial_kernel, grid, dim3(threads), (size_t)C * sizeof(float), stream, x, partials, T, C, groups, nchunks);
+    SD_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, dim3(threads), (size_t)groups * 2 * sizeof(float), stream, x, y, gamma, beta,
+                       partials, T, C, groups, nchunks, eps);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+}  // namespace sd

@@ -1,0 +1,215 @@
+// In-place LoRA patching for gfx950: W <- W + scale * (B A) over a list of fp32 matrices in
+// one grouped launch, with W's old bits saved to an undo record in the same pass, and the
+// inverse pass that copies them back (Section 4.2, "Efficient LoRA patching": merge into the
+// base parameters in place; take the adapter off after the request).
+//
+// HBM-bound: 4 B read + 4 B write (+ 4 B undo) per element against 2r FLOP, so the rank-r
+// product must not become the limit: it runs on the fp32 matrix cores (32x32x2 MFMA) while
+// the W loads of the same tile are in flight.  One wavefront owns 32 rows x 128 columns;
+// lane l holds columns c0 + 4*(l%32) + {0..3} of 16 rows, i.e. four MFMA column blocks
+// interleaved so that every W access is a 16-byte float4 and a wavefront load covers two
+// 512-byte row segments.
+#include "common.hpp"
+
+namespace sd {
+
+struct PatchPlanEntry {
+    sd_patch_desc d;       // 48 bytes
+    int64_t tile_begin;    // first workgroup tile of this matrix
+    int32_t tiles_c;       // column tiles (128 wide)
+    int32_t pad;
+};
+static_assert(sizeof(sd_patch_desc) == 48, "descriptor layout");
+static_assert(sizeof(PatchPlanEntry) == 64, "plan entry layout");
+
+constexpr int PT_ROWS = 128, PT_COLS = 128;   // workgroup tile: 4 wavefronts x 32 rows
+
+__device__ __forceinline__ int find_entry(const PatchPlanEntry* __restrict__ plan, int n, int64_t tile) {
+    int lo = 0, hi = n - 1;   // last entry with tile_begin <= tile
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (plan[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(256) void lora_patch_kernel(const PatchPlanEntry* __restrict__ plan, int n) {
+    const int64_t tile = blockIdx.x;
+    const PatchPlanEntry& E = plan[find_entry(plan, n, tile)];
+    const int out = E.d.out, in = E.d.in, r = E.d.r;
+    const float scale = E.d.scale;
+    float* __restrict__ W = E.d.W;
+    float* __restrict__ U = E.d.undo;
+    const float* __restrict__ A = E.d.A;
+    const float* __restrict__ B = E.d.B;
+    const int local = (int)(tile - E.tile_begin);
+    const int tc = local % E.tiles_c, tr = local / E.tiles_c;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int r0 = tr * PT_ROWS + wave * 32;
+    const int c0 = tc * PT_COLS;
+    if (r0 >= out) return;
+    const int col = c0 + 4 * l32;
+    const bool full = (r0 + 32 <= out) && (c0 + PT_COLS <= in) && ((in & 3) == 0);
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+    if (full) {
+        // W tile first: these loads stay in flight under the MFMA loop
+        float4 w[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            w[v] = *reinterpret_cast<const float4*>(W + (size_t)row * in + col);
+        }
+        const float* bp = B + (size_t)(r0 + l32) * r + hi;
+        const float* ap = A + (size_t)hi * in + col;
+        const int kp_n = r >> 1;
+#pragma unroll 4
+        for (int kp = 0; kp < kp_n; ++kp) {
+            const float bv = bp[2 * kp];
+            const float4 av = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+        }
+        if (r & 1) {   // odd rank: last k pairs with a zero
+            const int kk = r - 1;
+            const float bv = hi ? 0.f : B[(size_t)(r0 + l32) * r + kk];
+            float4 av = {0.f, 0.f, 0.f, 0.f};
+            if (!hi) av = *reinterpret_cast<const float4*>(A + (size_t)kk * in + col);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            const size_t idx = (size_t)row * in + col;
+            *reinterpret_cast<float4*>(U + idx) = w[v];
+            float4 o;
+            o.x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
+            o.y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
+            o.z = __fadd_rn(w[v].z, __fmul_rn(scale, acc[2][v]));
+            o.w = __fadd_rn(w[v].w, __fmul_rn(scale, acc[3][v]));
+            *reinterpret_cast<float4*>(W + idx) = o;
+        }
+    } else {
+        // ragged tile: same arithmetic, every access guarded and scalar
+        const int brow = r0 + l32;
+        const int kp_n = (r + 1) >> 1;
+#pragma unroll 1
+        for (int kp = 0; kp < kp_n; ++kp) {
+            const int kk = 2 * kp + hi;
+            const bool kv = kk < r;
+            const float bv = (kv && brow < out) ? B[(size_t)brow * r + kk] : 0.f;
+            float av[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) av[j] = (kv && col + j < in) ? A[(size_t)kk * in + col + j] : 0.f;
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[0], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[1], acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[2], acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[3], acc[3], 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            if (row >= out) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (col + j >= in) continue;
+                const size_t idx = (size_t)row * in + col + j;
+                const float wv = W[idx];
+                U[idx] = wv;
+                W[idx] = __fadd_rn(wv, __fmul_rn(scale, acc[j][v]));
+            }
+        }
+    }
+}
+
+// Unpatch: W <- undo, the same tiling, a pure copy.
+__global__ __launch_bounds__(256) void lora_unpatch_kernel(const PatchPlanEntry* __restrict__ plan, int n) {
+    const int64_t tile = blockIdx.x;
+    const PatchPlanEntry& E = plan[find_entry(plan, n, tile)];
+    const int out = E.d.out, in = E.d.in;
+    float* __restrict__ W = E.d.W;
+    const float* __restrict__ U = E.d.undo;
+    const int local = (int)(tile - E.tile_begin);
+    const int tc = local % E.tiles_c, tr = local / E.tiles_c;
+    const int c0 = tc * PT_COLS, r0 = tr * PT_ROWS;
+    const int tcol = (threadIdx.x & 31) * 4, trow = threadIdx.x >> 5;   // 8 rows per pass
+    const bool vec = ((in & 3) == 0) && (c0 + PT_COLS <= in);
+#pragma unroll 4
+    for (int i = 0; i < PT_ROWS / 8; ++i) {
+        const int row = r0 + trow + i * 8;
+        if (row >= out) break;
+        const size_t idx = (size_t)row * in + c0 + tcol;
+        if (vec) {
+            *reinterpret_cast<float4*>(W + idx) = *reinterpret_cast<const float4*>(U + idx);
+        } else {
+            for (int j = 0; j < 4; ++j)
+                if (c0 + tcol + j < in) W[idx + j] = U[idx + j];
+        }
+    }
+}
+
+}  // namespace sd
+
+using namespace sd;
+
+extern "C" size_t sd_patch_plan_bytes(int32_t n) { return n > 0 ? (size_t)n * sizeof(PatchPlanEntry) : 0; }
+
+extern "C" int sd_patch_plan_build(const sd_patch_desc* descs, int32_t n, void* plan_host, size_t plan_bytes,
+                                   int64_t* total_tiles) {
+    SD_REQUIRE(n >= 0, SD_EINVAL, "patch plan: n=%d", n);
+    SD_REQUIRE(total_tiles, SD_EINVAL, "patch plan: total_tiles is null");
+    *total_tiles = 0;
+    if (n == 0) return SD_OK;
+    SD_REQUIRE(descs && plan_host, SD_EINVAL, "patch plan: null pointer");
+    SD_REQUIRE(plan_bytes >= sd_patch_plan_bytes(n), SD_EWORKSPACE, "patch plan: buffer of %zu bytes, need %zu", plan_bytes,
+               sd_patch_plan_bytes(n));
+    PatchPlanEntry* plan = static_cast<PatchPlanEntry*>(plan_host);
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const sd_patch_desc& d = descs[i];
+        SD_REQUIRE(d.W && d.A && d.B && d.undo, SD_EINVAL, "patch desc %d: null pointer (W, A, B and undo are required)", i);
+        SD_REQUIRE(aligned16(d.W) && aligned16(d.A) && aligned16(d.B) && aligned16(d.undo), SD_EINVAL,
+                   "patch desc %d: pointers must be 16-byte aligned", i);
+        SD_REQUIRE(d.out > 0 && d.in > 0 && d.r > 0 && d.r <= 1024, SD_EINVAL, "patch desc %d: out=%d in=%d r=%d", i, d.out, d.in, d.r);
+        SD_REQUIRE(d.undo != d.W, SD_EINVAL, "patch desc %d: undo aliases W", i);
+        plan[i].d = d;
+        plan[i].tile_begin = total;
+        plan[i].tiles_c = (d.in + PT_COLS - 1) / PT_COLS;
+        plan[i].pad = 0;
+        total += (int64_t)plan[i].tiles_c * ((d.out + PT_ROWS - 1) / PT_ROWS);
+    }
+    SD_REQUIRE(total < (int64_t)0x7fffffff, SD_EUNSUPPORTED, "patch plan: %lld tiles exceed one grid", (long long)total);
+    *total_tiles = total;
+    return SD_OK;
+}
+
+static int patch_launch(bool undo, const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    SD_REQUIRE(n >= 0 && total_tiles >= 0, SD_EINVAL, "patch: n=%d tiles=%lld", n, (long long)total_tiles);
+    if (n == 0 || total_tiles == 0) return SD_OK;
+    SD_REQUIRE(plan_dev, SD_EINVAL, "patch: plan is null");
+    SD_REQUIRE(total_tiles < (int64_t)0x7fffffff, SD_EUNSUPPORTED, "patch: %lld tiles exceed one grid", (long long)total_tiles);
+    const PatchPlanEntry* plan = static_cast<const PatchPlanEntry*>(plan_dev);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (undo) hipLaunchKernelGGL(lora_unpatch_kernel, dim3((unsigned)total_tiles), dim3(256), 0, s, plan, n);
+    else hipLaunchKernelGGL(lora_patch_kernel, dim3((unsigned)total_tiles), dim3(256), 0, s, plan, n);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+extern "C" int sd_lora_patch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    return patch_launch(false, plan_dev, n, total_tiles, stream);
+}
+extern "C" int sd_lora_unpatch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    return patch_launch(true, plan_dev, n, total_tiles, stream);
+}
