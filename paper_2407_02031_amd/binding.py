@@ -16,7 +16,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libswiftdiff.so")
+LIB_PATH = os.environ.get("SWIFTDIFF_LIB") or os.path.join(_HERE, "libswiftdiff.so")
 
 SD_BF16, SD_F32 = 0, 1
 SD_EPI_NONE, SD_EPI_GEGLU = 0, 1

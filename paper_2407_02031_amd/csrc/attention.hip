@@ -18,20 +18,30 @@ namespace sd {
 
 __device__ __forceinline__ int aswz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
+constexpr float RESCALE_LOG2 = 8.0f;
+
 template <int QB>
 __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
                                                         const uint16_t* __restrict__ k, int64_t ldk,
                                                         const uint16_t* __restrict__ vt, int64_t ldvt,
                                                         uint16_t* __restrict__ out, int64_t ldo,
-                                                        int Tq, int Tk, int Tkp, float c) {
+                                                        int Tq, int Tk, int Tkp, int heads, int qtiles, float c) {
     constexpr int BQ = 4 * 32 * QB;
-    __shared__ u32x4 ldsK[2][64 * 8];   // [key][8 chunks of 8 d]
-    __shared__ u32x4 ldsV[2][64 * 8];   // [d][8 chunks of 8 keys]
+    __shared__ u32x4 ldsK[2][64 * 8];   // [key][8 chunks of 8 d], 2-deep ring
+    __shared__ u32x4 ldsV[3][64 * 8];   // [d][8 chunks of 8 keys, key order permuted], 3-deep ring
 
-    const int head = blockIdx.y, b = blockIdx.z;
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
+    // (sample, head, query tile) so that one head's K and V stay in one XCD's L2.
+    const int total = gridDim.x;
+    int wi = blockIdx.x;
+#ifndef EXP_NOREMAP
+    if ((total & 7) == 0) wi = (wi & 7) * (total >> 3) + (wi >> 3);
+#endif
+    const int qt = wi % qtiles;
+    const int head = (wi / qtiles) % heads, b = wi / (qtiles * heads);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
-    const int q0 = blockIdx.x * BQ + wave * 32 * QB;
+    const int q0 = qt * BQ + wave * 32 * QB;
 
     // ---- Q fragments (B operand of S^T = K Q^T): lane holds q[row l32][d = kk*16 + hi*8 ..+8]
     bf16x8 qf[QB][4];
@@ -74,12 +84,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             rv[i] = v;
         }
     };
-    auto store_kv = [&](int buf) {
+    // K rows go in as they are.  V^T rows are stored with the keys of every 16-key group
+    // permuted to [0-3, 8-11, 4-7, 12-15], the order in which the score accumulator of one
+    // half-wavefront holds them, so the MFMA operand is a single 16-byte read.
+    auto store_kv = [&](int kslot, int vslot) {
+        u32x2* lv2 = reinterpret_cast<u32x2*>(ldsV[vslot]);
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int r = lrow + i * 32;
-            ldsK[buf][r * 8 + aswz(r, lc)] = rk[i];
-            ldsV[buf][r * 8 + aswz(r, lc)] = rv[i];
+            ldsK[kslot][r * 8 + aswz(r, lc)] = rk[i];
+            const int c0 = aswz(r, lc & ~1);           // physical chunk of the group's first half
+            const int c1 = c0 ^ 1;
+            const u32x2 lo = {rv[i][0], rv[i][1]}, hh = {rv[i][2], rv[i][3]};
+            lv2[(r * 8 + c0) * 2 + (lc & 1)] = lo;
+            lv2[(r * 8 + c1) * 2 + (lc & 1)] = hh;
         }
     };
 
@@ -95,20 +113,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             for (int v = 0; v < 16; ++v) o[qb][db][v] = 0.f;
     }
 
-    const int nt = (Tk + 63) >> 6;
-    load_kv(0);
-    store_kv(0);
-    __syncthreads();
-
-#pragma unroll 1
-    for (int t = 0; t < nt; ++t) {
-        const bool more = t + 1 < nt;
-        if (more) load_kv(t + 1);
+    // S^T tile of key tile t: 64 keys x (32*QB) queries
+    auto compute_s = [&](int t, f32x16 (&s)[QB][2]) {
         const u32x4* lk = ldsK[t & 1];
-        const u32x2* lv = reinterpret_cast<const u32x2*>(ldsV[t & 1]);
-
-        // ---- S^T tile: 64 keys x (32*QB) queries
-        f32x16 s[QB][2];
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -116,66 +123,79 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[qb][kb][v] = 0.f;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int kb = 0; kb < 2; ++kb) {
                 const int r = kb * 32 + l32;
                 const bf16x8 a = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, kk * 2 + hi)]);
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
                     s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], s[qb][kb], 0, 0, 0);
             }
-        // mask the keys past Tk (last tile only)
-        if (t * 64 + 64 > Tk) {
+    };
+    // keys past Tk (last tile only) get a score of -inf
+    auto mask_tail = [&](int t, f32x16 (&s)[QB][2]) {
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
-                    if (key >= Tk) {
+            for (int v = 0; v < 16; ++v) {
+                const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                if (key >= Tk) {
 #pragma unroll
-                        for (int qb = 0; qb < QB; ++qb) s[qb][kb][v] = -INFINITY;
-                    }
+                    for (int qb = 0; qb < QB; ++qb) s[qb][kb][v] = -INFINITY;
                 }
-        }
-
-        // ---- online softmax; this lane's query is column l32, its keys are its registers
-        bf16x8 pf[QB][2][2];
+            }
+    };
+    // running-maximum bookkeeping of one tile: the reference maximum m only moves when the
+    // tile maximum exceeds it by more than RESCALE_LOG2 in the exponent (p <= 2^RESCALE_LOG2
+    // stays far inside fp32 / bf16 range), so the O and l rescale runs on the first tiles and
+    // almost never afterwards.  This lane's query is column l32, its keys are its registers.
+    auto update_max = [&](f32x16 (&s)[QB][2]) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-            float mx = s[qb][0][0];
+            float mx = fmaxf(s[qb][0][0], s[qb][1][0]);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[qb][kb][v]);
+            for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[qb][0][v]), s[qb][1][v]);
             mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float mnew = fmaxf(m[qb], mx);
-            const float alpha = __builtin_amdgcn_exp2f((m[qb] - mnew) * c);
-            m[qb] = mnew;
-            const float mc = mnew * c;
+            const bool need = (mx - m[qb]) * c > RESCALE_LOG2;
+            if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
+                const float mnew = need ? mx : m[qb];
+                const float alpha = __builtin_amdgcn_exp2f((m[qb] - mnew) * c);
+                m[qb] = mnew;
+                l[qb] *= alpha;
+#pragma unroll
+                for (int db = 0; db < 2; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[qb][db][v] *= alpha;
+            }
+        }
+    };
+    // p = exp2((s - m) * c) packed to bf16 in MFMA operand order, row sums into l
+    auto exponentials = [&](f32x16 (&s)[QB][2], bf16x8 (&pf)[QB][2][2]) {
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+            const float mc = m[qb] * c;
             float ls = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int g2 = 0; g2 < 2; ++g2) {
-                    u32x4 pk;
+                    bf16x8 pk;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float p0 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e] * c - mc);
-                        const float p1 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e + 1] * c - mc);
-                        ls += p0 + p1;
-                        pk[e] = pack_bf16x2(p0, p1);
+                    for (int e = 0; e < 8; ++e) {
+                        const float p = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + e] * c - mc);
+                        ls += p;
+                        pk[e] = (__bf16)p;
                     }
-                    pf[qb][kb][g2] = __builtin_bit_cast(bf16x8, pk);
+                    pf[qb][kb][g2] = pk;
                 }
-            l[qb] = l[qb] * alpha + ls;
-#pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[qb][db][v] *= alpha;
+            l[qb] += ls;
         }
-
-        // ---- O^T += V^T P^T.  k-slot j of sub-step (kb, g2) is key kb*32 + 16*g2 + 8*(j/4) + 4*hi + j%4
+    };
+    // O^T += V^T P^T.  k-slot j of sub-step (kb, g2) is key kb*32 + 16*g2 + 8*(j/4) + 4*hi + j%4,
+    // which is the 16-byte piece (2*(kb*2+g2) + hi) of the permuted V^T row
+    auto accumulate_o = [&](int vslot, bf16x8 (&pf)[QB][2][2]) {
+        const u32x4* lv = ldsV[vslot];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -183,19 +203,68 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
 #pragma unroll
                 for (int db = 0; db < 2; ++db) {
                     const int r = db * 32 + l32;
-                    const int ch = kb * 4 + g2 * 2;
-                    const u32x2 lo = lv[(r * 8 + aswz(r, ch)) * 2 + hi];
-                    const u32x2 hh = lv[(r * 8 + aswz(r, ch + 1)) * 2 + hi];
-                    const u32x4 av = {lo[0], lo[1], hh[0], hh[1]};
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, lv[r * 8 + aswz(r, kb * 4 + g2 * 2 + hi)]);
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb)
                         o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[qb][kb][g2], o[qb][db], 0, 0, 0);
                 }
+    };
 
-        if (more) store_kv((t + 1) & 1);
-        __syncthreads();
+    // ---- prologue: tiles 0 and 1 into LDS, S of tile 0
+    const int nt = (Tk + 63) >> 6;
+    load_kv(0);
+    store_kv(0, 0);
+    if (nt > 1) {
+        load_kv(1);
+        store_kv(1, 1);
     }
+    __syncthreads();
+    f32x16 sc[QB][2], sn[QB][2];
+    compute_s(0, sc);
+
+    // ---- main loop, software-pipelined: the score MFMAs of tile t+1 are independent of the
+    // exponentials of tile t and sit in the same basic block, so the matrix pipe and the
+    // vector ALU overlap inside one wavefront.  The last tile is peeled (nothing to prefetch,
+    // and it is the only one that may need masking).
+    int vslot = 0;
+    bf16x8 pf[QB][2][2];
+#pragma unroll 1
+    for (int t = 0; t + 1 < nt; ++t) {
+#ifdef EXP_NOLOAD
+        const bool pre = false;
+#else
+        const bool pre = t + 2 < nt;
+#endif
+        if (pre) load_kv(t + 2);
+#ifndef EXP_NOMAX
+        update_max(sc);
+#endif
+#ifndef EXP_NOS
+        compute_s(t + 1, sn);
+#endif
+#ifndef EXP_NOEXPS
+        exponentials(sc, pf);
+#endif
+#ifndef EXP_NOPV
+        accumulate_o(vslot, pf);
+#endif
+        // tile t+2: K slot t%2 was last read for S(t) one iteration ago, V slot (t+2)%3 for
+        // tile t-1: both free since the previous barrier
+        const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
+        if (pre) store_kv(t & 1, vnext2);
+        vslot = vslot == 2 ? 0 : vslot + 1;
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) sc[qb][kb] = sn[qb][kb];
+#ifndef EXP_NOBAR
+        __syncthreads();
+#endif
+    }
+    if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sc);
+    update_max(sc);
+    exponentials(sc, pf);
+    accumulate_o(vslot, pf);
 
     // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
 #pragma unroll
@@ -209,10 +278,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             for (int db = 0; db < 2; ++db)
 #pragma unroll
                 for (int v4 = 0; v4 < 4; ++v4) {
-                    u32x2 w;
-                    w[0] = pack_bf16x2(o[qb][db][4 * v4] * inv, o[qb][db][4 * v4 + 1] * inv);
-                    w[1] = pack_bf16x2(o[qb][db][4 * v4 + 2] * inv, o[qb][db][4 * v4 + 3] * inv);
-                    *reinterpret_cast<u32x2*>(op + db * 32 + 8 * v4) = w;
+                    bf16x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[qb][db][4 * v4 + e] * inv);
+                    *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * v4) = w;
                 }
         }
     }
@@ -226,13 +295,9 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
     if (Bn <= 0 || Tq <= 0 || heads <= 0) return SD_OK;
     const float c = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
-    if (Tq >= 2048) {
-        dim3 grid((Tq + 255) / 256, heads, Bn);
-        hipLaunchKernelGGL(attention_kernel<2>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, c);
-    } else {
-        dim3 grid((Tq + 127) / 128, heads, Bn);
-        hipLaunchKernelGGL(attention_kernel<1>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, c);
-    }
+    const int qtiles = (Tq + 127) / 128;
+    dim3 grid((unsigned)(qtiles * heads * Bn));
+    hipLaunchKernelGGL(attention_kernel<1>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, heads, qtiles, c);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
