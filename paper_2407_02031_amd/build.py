@@ -21,7 +21,7 @@ SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "patch.hip"]
 EXTRA = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=default",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-pass-failed"]
+         "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option", "-Wno-pass-failed", "-Wno-inline-asm"]
 
 
 def _hipcc() -> str:

@@ -7,27 +7,77 @@
 // bias, exact-erf GEGLU (Section 4.3's fused GEGLU), residual add, bf16 or fp32 store.
 //
 // Tiling: BM x BN output tile per workgroup, BK = 64, WGM x WGN wavefronts, each owning
-// (BM/WGM) x (BN/WGN) as 32x32x16 bf16 MFMA tiles with fp32 accumulators.  Operand tiles
-// go global -> registers -> LDS (16-byte chunks, XOR-swizzled so that the 32 rows one
-// MFMA operand read touches fall in distinct banks) and are double-buffered: the global
-// loads of tile t+1 are in flight while tile t is multiplied.
+// (BM/WGM) x (BN/WGN) as 32x32x16 bf16 MFMA tiles with fp32 accumulators.
+// Pipeline: operand tiles go global -> registers -> LDS (16-byte chunks, XOR-swizzled so
+// the 32 rows one MFMA operand read touches fall in distinct banks).  Two register sets
+// keep the loads of tiles t+1 and t+2 in flight while tile t is multiplied out of a
+// two-deep LDS ring; inside a tile the operand fragments of k-step kk+1 are read from LDS
+// while the MFMAs of k-step kk run.  The epilogue stages each 32-row block of a wave's
+// accumulators through LDS so that global stores (and residual loads) are 16-byte rows.
 #include "common.hpp"
+
+#include <type_traits>
 
 namespace sd {
 
 __device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
 
-template <int BM, int BN, int WGM, int WGN, bool GEGLU>
+// erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7), far below bf16 resolution
+__device__ __forceinline__ float erf_as(float x) {
+    const float ax = fabsf(x);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    p *= t;
+    const float e = __builtin_amdgcn_exp2f(-1.44269504088896340736f * ax * ax);
+    const float r = fmaf(-p, e, 1.0f);
+    return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.0f + erf_as(z * 0.70710678118654752440f)); }
+
+constexpr int EPI_STRIDE = 72;   // floats per staged row: 4 rows apart differ by 128 B mod 256 (no bank overlap)
+
+// 256 bytes of zeros: where the lanes of a direct-to-LDS load point when their chunk lies
+// past the end of a K segment (the load itself cannot zero-fill)
+__device__ __attribute__((aligned(256))) uint32_t g_gemm_zeros[64];
+
+// One direct global -> LDS load: every lane fetches 16 bytes from its own global address and
+// the wavefront's 64 pieces land contiguously at LDS byte address `lds_base` (wave-uniform).
+// Written as inline assembly so that the compiler does not serialise the LDS reads of the
+// tile being multiplied behind loads that target another ring stage; completion is tracked
+// by hand with vmcnt (loads retire in order) and a workgroup barrier.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int BM, int BN, int WGM, int WGN, int STAGES>
+constexpr int gemm_lds_chunks() {
+    constexpr int ring = STAGES * (BM + BN) * 8;
+    constexpr int epi = WGM * WGN * 32 * EPI_STRIDE / 4;
+    return ring > epi ? ring : epi;
+}
+
+// GUARD: K segments that are not multiples of 64 (tail chunks read zeros).
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g) {
-    constexpr int NT = 64 * WGM * WGN;
+    constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
-    constexpr int CHA = BM * 8 / NT, CHB = BN * 8 / NT;
-    constexpr int RSTEP = NT / 8;   // rows between two chunks of one thread
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads mismatch");
+    constexpr int NBLK = (BM + BN) / 8;        // 1 KB blocks (8 rows x 128 B) per stage
+    constexpr int LPT = NBLK / NW;             // direct-to-LDS loads per wave (= per lane) per tile
+    constexpr int STAGE = (BM + BN) * 8;       // 16-byte chunks per stage
+    constexpr int DIST = STAGES - 1;           // tiles in flight ahead of the one being multiplied
+    static_assert(NBLK % NW == 0, "tile/waves mismatch");
     static_assert(!GEGLU || (NI % 2 == 0), "GEGLU needs value/gate column-block pairs per wave");
+    static_assert(DIST >= 1 && DIST <= 2, "ring depth");
 
-    __shared__ u32x4 lds[2][(BM + BN) * 8];
+    __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, WGM, WGN, STAGES>()];
 
     // ---- which problem, which tile ----
     const int tile = blockIdx.x;
@@ -43,10 +93,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
     const int Mp = P.Mp, N = P.N, K0 = P.K0, K1 = P.K1;
     const int nk0 = (K0 + 63) >> 6, nk1 = (K1 + 63) >> 6, nkt = nk0 + nk1;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
-    const int lrow = tid >> 3, lc = tid & 7;
 
     // Q-operand (weight) row of tile row j.  GEGLU: 32-row blocks alternate value / gate
     // rows of the same 32 output columns, so one lane ends up holding both halves.
@@ -62,42 +112,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
         }
     };
 
-    const uint16_t* pa[CHA];
-    const uint16_t* pb[CHB];
+    // ---- loader.  Load j of wave w fills 1 KB block (j*NW + w) of a stage: 8 tile rows
+    // (P rows first, then Q rows) of 8 chunks; lane l lands at chunk position l&7 of row
+    // l>>3, so it must fetch the logical chunk that the XOR swizzle places there.
+    const uint16_t* gp[LPT];     // this lane's source (row start + chunk) per load, current segment
+    int kcol[LPT];               // first k of that chunk within a 64-deep tile
     auto setup = [&](int seg) {
         const uint16_t* pbase = seg ? P.p1 : P.p0;
         const uint16_t* qbase = seg ? P.q1 : P.q0;
         const int64_t ldp = seg ? P.ldp1 : P.ldp0, ldq = seg ? P.ldq1 : P.ldq0;
 #pragma unroll
-        for (int i = 0; i < CHA; ++i) {
-            int r = m0 + lrow + i * RSTEP;
-            r = r < Mp ? r : Mp - 1;
-            pa[i] = pbase + (int64_t)r * ldp + lc * 8;
+        for (int j = 0; j < LPT; ++j) {
+            const int row = (j * NW + wave) * 8 + (lane >> 3);     // row within the stage
+            const int c = (lane & 7) ^ ((row >> 1) & 7);           // logical chunk fetched by this lane
+            kcol[j] = c * 8;
+            if (row < BM) {
+                int r = m0 + row;
+                r = r < Mp ? r : Mp - 1;
+                gp[j] = pbase + (int64_t)r * ldp + c * 8;
+            } else {
+                gp[j] = qbase + (int64_t)qrow(row - BM) * ldq + c * 8;
+            }
         }
-#pragma unroll
-        for (int i = 0; i < CHB; ++i) pb[i] = qbase + (int64_t)qrow(lrow + i * RSTEP) * ldq + lc * 8;
     };
-
-    u32x4 ra[CHA], rb[CHB];
-    auto load_tile = [&](int t) {
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+    auto issue_tile = [&](int t) {
         if (t == nk0) setup(1);
         const int kt = t < nk0 ? t : t - nk0;
         const int Kseg = t < nk0 ? K0 : K1;
         const int kb = kt * 64;
-        const bool kval = kb + lc * 8 < Kseg;   // K segments are multiples of 8
-        const u32x4 zero = {0u, 0u, 0u, 0u};
+        const uint32_t sbase = lds_base + (uint32_t)(t % STAGES) * (STAGE * 16) + (uint32_t)wave * 1024;
 #pragma unroll
-        for (int i = 0; i < CHA; ++i) ra[i] = kval ? *reinterpret_cast<const u32x4*>(pa[i] + kb) : zero;
-#pragma unroll
-        for (int i = 0; i < CHB; ++i) rb[i] = kval ? *reinterpret_cast<const u32x4*>(pb[i] + kb) : zero;
-    };
-    auto store_lds = [&](int buf) {
-        u32x4* la = lds[buf];
-        u32x4* lb = lds[buf] + BM * 8;
-#pragma unroll
-        for (int i = 0; i < CHA; ++i) { int r = lrow + i * RSTEP; la[r * 8 + swz(r, lc)] = ra[i]; }
-#pragma unroll
-        for (int i = 0; i < CHB; ++i) { int r = lrow + i * RSTEP; lb[r * 8 + swz(r, lc)] = rb[i]; }
+        for (int j = 0; j < LPT; ++j) {
+            const void* src = gp[j] + kb;
+            if (GUARD) src = (kb + kcol[j] < Kseg) ? src : (const void*)g_gemm_zeros;
+            dma16(src, sbase + (uint32_t)j * (NW * 1024));
+        }
     };
 
     f32x16 acc[MI][NI];
@@ -108,94 +158,152 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    setup(0);
-    load_tile(0);
-    store_lds(0);
-    __syncthreads();
-
-#pragma unroll 1
-    for (int t = 0; t < nkt; ++t) {
-        const bool more = t + 1 < nkt;
-        if (more) load_tile(t + 1);
-        const u32x4* la = lds[t & 1];
-        const u32x4* lb = lds[t & 1] + BM * 8;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 af[MI], bfr[NI];
+    // one 64-deep tile out of ring stage `st`; fragments of k-step kk+1 are fetched while
+    // the MFMAs of k-step kk execute
+    auto compute = [&](int st) {
+        const u32x4* la = lds + st * STAGE;
+        const u32x4* lb = la + BM * 8;
+        bf16x8 af[2][MI], bfr[2][NI];
+        auto fetch = [&](int kk, int fs) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
-                int r = wm + mi * 32 + l32;
-                af[mi] = __builtin_bit_cast(bf16x8, la[r * 8 + swz(r, kk * 2 + hi)]);
+                const int r = wm + mi * 32 + l32;
+                af[fs][mi] = __builtin_bit_cast(bf16x8, la[r * 8 + swz(r, kk * 2 + hi)]);
             }
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
-                int r = wn + ni * 32 + l32;
-                bfr[ni] = __builtin_bit_cast(bf16x8, lb[r * 8 + swz(r, kk * 2 + hi)]);
+                const int r = wn + ni * 32 + l32;
+                bfr[fs][ni] = __builtin_bit_cast(bf16x8, lb[r * 8 + swz(r, kk * 2 + hi)]);
             }
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk < 3) fetch(kk + 1, (kk + 1) & 1);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-        }
-        if (more) store_lds((t + 1) & 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue.  Accumulator layout of the 32x32 MFMA: lane holds column l32 and rows
-    // 8*(v/4) + 4*hi + (v%4), v = 0..15. ----
-    const float alpha = P.alpha;
-    const uint16_t* bias = P.bias;
-    auto emit = [&](int p, int q, float val) {
-        if (p >= Mp || q >= N) return;
-        if (bias) val += bf16_to_f32(bias[P.bias_on_rows ? p : q]);
-        const int64_t oi = (int64_t)p * P.ldy + q;
-        if (P.y_f32) {
-            if (P.res) val += static_cast<const float*>(P.res)[(int64_t)p * P.ldr + q];
-            static_cast<float*>(P.y)[oi] = val;
-        } else {
-            if (P.res) val += bf16_to_f32(static_cast<const uint16_t*>(P.res)[(int64_t)p * P.ldr + q]);
-            static_cast<uint16_t*>(P.y)[oi] = (uint16_t)f32_to_bf16_bits(val);
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
         }
     };
-    if constexpr (GEGLU) {
+
+    // ---- prologue: the first DIST tiles in flight
+    setup(0);
+    issue_tile(0);
+    if (DIST > 1 && nkt > 1) issue_tile(1);
+
+    // ---- main loop.  Step t: wait until this wave's loads of tile t have landed (loads of
+    // newer tiles may stay in flight), barrier (every wave's part of tile t is in LDS and
+    // every wave is done reading the stage of tile t-1), refill that stage with tile t+DIST,
+    // multiply tile t.
+    int st = 0;
+#pragma unroll 1
+    for (int t = 0; t < nkt; ++t) {
+        if (DIST > 1 && t + 1 < nkt) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
+        __syncthreads();
+        if (t + DIST < nkt) issue_tile(t + DIST);
+        compute(st);
+        st = st + 1 == STAGES ? 0 : st + 1;
+    }
+    __syncthreads();   // ring reads done before the epilogue reuses LDS
+
+    // ---- epilogue.  Accumulator layout of the 32x32 MFMA: lane holds column l32 and rows
+    // 8*(v/4) + 4*hi + (v%4), v = 0..15.  Each wave stages one 32-row block at a time in its
+    // own LDS region (fp32, padded rows) and writes it out as 16-byte row pieces.
+    float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
+    const float alpha = P.alpha;
+    const uint16_t* bias = P.bias;
+    constexpr int NOUT = GEGLU ? NI / 2 : NI;   // 32-column output blocks per wave
+    constexpr int WCOLS = NOUT * 32;            // output columns per wave
+    constexpr int LPR = WCOLS / 4;              // lanes per staged row (4 columns each)
+    constexpr int RPP = 64 / LPR;               // rows per pass
+    const int wn_out = GEGLU ? (wn >> 1) : wn;
+    const bool y_f32 = P.y_f32 != 0;
+    const int lr = lane / LPR, lcol = (lane % LPR) * 4;
+    const int q4 = n0 + wn_out + lcol;
+    // 16-byte path: whole 4-column piece inside N and rows 16-byte aligned
+    const bool vec_ok = (q4 + 4 <= N) && ((P.ldy & 3) == 0) && (!P.res || (P.ldr & 3) == 0);
+
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+    for (int mi = 0; mi < MI; ++mi) {
+        // 1) registers -> staging (value after alpha, bias, GEGLU)
 #pragma unroll
-            for (int nj = 0; nj < NI / 2; ++nj) {
-                const int q = n0 + (wn >> 1) + nj * 32 + l32;
-                float bv = 0.f, bg = 0.f;
-                if (bias && q < N) { bv = bf16_to_f32(bias[q]); bg = bf16_to_f32(bias[q + P.geglu_F]); }
+        for (int nj = 0; nj < NOUT; ++nj) {
+            const int q = n0 + wn_out + nj * 32 + l32;
+            float bv = 0.f, bg = 0.f;
+            if (bias && !P.bias_on_rows && q < N) {
+                bv = bf16_to_f32(bias[q]);
+                if (GEGLU) bg = bf16_to_f32(bias[q + P.geglu_F]);
+            }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int p = m0 + wm + mi * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
-                    if (p < Mp && q < N) {
-                        float val = alpha * acc[mi][2 * nj][v] + bv;
-                        float gate = alpha * acc[mi][2 * nj + 1][v] + bg;
-                        float ge = 0.5f * gate * (1.0f + erff(gate * 0.70710678118654752440f));
-                        float o = val * ge;
-                        const int64_t oi = (int64_t)p * P.ldy + q;
-                        if (P.y_f32) static_cast<float*>(P.y)[oi] = o;
-                        else static_cast<uint16_t*>(P.y)[oi] = (uint16_t)f32_to_bf16_bits(o);
+            for (int v = 0; v < 16; ++v) {
+                const int rr = 8 * (v >> 2) + 4 * hi + (v & 3);
+                float val;
+                if (GEGLU) {
+                    const float a = alpha * acc[mi][2 * nj][v] + bv;
+                    const float gt = alpha * acc[mi][2 * nj + 1][v] + bg;
+                    val = a * gelu_erf(gt);
+                } else {
+                    val = alpha * acc[mi][nj][v] + bv;
+                }
+                stage[rr * EPI_STRIDE + nj * 32 + l32] = val;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        // 2) staging -> global: lane handles 4 consecutive columns of one row per pass
+#pragma unroll 2
+        for (int pass = 0; pass < 32 / RPP; ++pass) {
+            const int rr = pass * RPP + lr;
+            const int p = m0 + wm + mi * 32 + rr;
+            if (p < Mp && q4 < N) {
+                f32x4 val = *reinterpret_cast<const f32x4*>(stage + rr * EPI_STRIDE + lcol);
+                if (bias && P.bias_on_rows) val += bf16_to_f32(bias[p]);
+                const int64_t oi = (int64_t)p * P.ldy + q4;
+                const int64_t ri = (int64_t)p * P.ldr + q4;
+                if (y_f32) {
+                    float* yp = static_cast<float*>(P.y) + oi;
+                    const float* rp = static_cast<const float*>(P.res);
+                    if (vec_ok) {
+                        if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
+                        *reinterpret_cast<f32x4*>(yp) = val;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (q4 + e < N) yp[e] = val[e] + (rp ? rp[ri + e] : 0.f);
+                    }
+                } else {
+                    uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
+                    const uint16_t* rp = static_cast<const uint16_t*>(P.res);
+                    if (vec_ok) {
+                        if (rp) {
+                            const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
+                            val[0] += bf16lo_to_f32(rv[0]); val[1] += bf16hi_to_f32(rv[0]);
+                            val[2] += bf16lo_to_f32(rv[1]); val[3] += bf16hi_to_f32(rv[1]);
+                        }
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
+                        *reinterpret_cast<bf16x4*>(yp) = o;
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (q4 + e < N) {
+                                const float f = val[e] + (rp ? bf16_to_f32(rp[ri + e]) : 0.f);
+                                yp[e] = __builtin_bit_cast(uint16_t, (__bf16)f);
+                            }
                     }
                 }
             }
-    } else {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int p = m0 + wm + mi * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
-                    const int q = n0 + wn + ni * 32 + l32;
-                    emit(p, q, alpha * acc[mi][ni][v]);
-                }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool GEGLU>
-static int launch_cfg(GemmGroup& g, hipStream_t stream) {
+template <int BM, int BN, int WGM, int WGN, int STAGES, bool GEGLU>
+static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
     int total = 0;
     for (int i = 0; i < g.n; ++i) {
@@ -207,7 +315,10 @@ static int launch_cfg(GemmGroup& g, hipStream_t stream) {
     }
     g.total_tiles = total;
     if (total == 0) return SD_OK;
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, GEGLU>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+    if (guard)
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, GEGLU, true>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+    else
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, GEGLU, false>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
@@ -215,7 +326,8 @@ static int launch_cfg(GemmGroup& g, hipStream_t stream) {
 int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     SD_REQUIRE(g.n >= 1 && g.n <= GEMM_MAX_PROBLEMS, SD_EINVAL, "gemm group: %d problems", g.n);
     bool geglu = g.p[0].geglu_F > 0;
-    long tiles128 = 0, tiles256 = 0;
+    bool guard = false;
+    long tiles256 = 0;
     int maxN = 0;
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
@@ -226,8 +338,8 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         SD_REQUIRE(P.ldp0 % 8 == 0 && P.ldq0 % 8 == 0 && (P.K1 == 0 || (P.ldp1 % 8 == 0 && P.ldq1 % 8 == 0)), SD_EINVAL,
                    "gemm problem %d: leading dimensions must be multiples of 8", i);
         if (P.Mp == 0 || P.N == 0) continue;
+        if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
         int bo = geglu ? 64 : 128;
-        tiles128 += (long)((P.Mp + 127) / 128) * ((P.N + bo - 1) / bo);
         tiles256 += (long)((P.Mp + 255) / 256) * ((P.N + bo - 1) / bo);
         if (P.N > maxN) maxN = P.N;
     }
@@ -238,12 +350,12 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     g.n = w;
     if (w == 0) return SD_OK;
     if (geglu) {
-        if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, true>(g, stream);
-        return launch_cfg<128, 128, 2, 2, true>(g, stream);
+        if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, true>(g, guard, stream);
+        return launch_cfg<128, 128, 2, 2, 2, true>(g, guard, stream);
     }
-    if (maxN <= 64) return launch_cfg<64, 64, 2, 2, false>(g, stream);
-    if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, false>(g, stream);
-    return launch_cfg<128, 128, 2, 2, false>(g, stream);
+    if (maxN <= 64) return launch_cfg<64, 64, 2, 2, 3, false>(g, guard, stream);
+    if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, false>(g, guard, stream);
+    return launch_cfg<128, 128, 2, 2, 2, false>(g, guard, stream);
 }
 
 }  // namespace sd
