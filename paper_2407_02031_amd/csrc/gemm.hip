@@ -75,7 +75,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
     constexpr int DIST = STAGES - 1;           // tiles in flight ahead of the one being multiplied
     static_assert(NBLK % NW == 0, "tile/waves mismatch");
     static_assert(!GEGLU || (NI % 2 == 0), "GEGLU needs value/gate column-block pairs per wave");
-    static_assert(DIST >= 1 && DIST <= 2, "ring depth");
+    static_assert(DIST >= 1 && DIST <= 4, "ring depth");
 
     __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, WGM, WGN, STAGES>()];
 
@@ -190,8 +190,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
 
     // ---- prologue: the first DIST tiles in flight
     setup(0);
-    issue_tile(0);
-    if (DIST > 1 && nkt > 1) issue_tile(1);
+#pragma unroll
+    for (int d = 0; d < DIST; ++d)
+        if (d < nkt) issue_tile(d);
 
     // ---- main loop.  Step t: wait until this wave's loads of tile t have landed (loads of
     // newer tiles may stay in flight), barrier (every wave's part of tile t is in LDS and
@@ -200,10 +201,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
     int st = 0;
 #pragma unroll 1
     for (int t = 0; t < nkt; ++t) {
-        if (DIST > 1 && t + 1 < nkt) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
+        {   // newer tiles already issued: min(DIST - 1, nkt - 1 - t)
+            const int newer = nkt - 1 - t;
+            if (DIST >= 4 && newer >= 3) wait_vmcnt<3 * LPT>();
+            else if (DIST >= 3 && newer >= 2) wait_vmcnt<2 * LPT>();
+            else if (DIST >= 2 && newer >= 1) wait_vmcnt<LPT>();
+            else wait_vmcnt<0>();
+        }
         __syncthreads();
+#ifndef EXP_NOLOAD
         if (t + DIST < nkt) issue_tile(t + DIST);
+#endif
+#ifndef EXP_NOCOMPUTE
         compute(st);
+#endif
         st = st + 1 == STAGES ? 0 : st + 1;
     }
     __syncthreads();   // ring reads done before the epilogue reuses LDS
@@ -349,11 +360,14 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (g.p[i].Mp > 0 && g.p[i].N > 0) { if (w != i) g.p[w] = g.p[i]; ++w; }
     g.n = w;
     if (w == 0) return SD_OK;
+    // 128x128 tiles, two workgroups per CU: with K of a few hundred the fill latency of the
+    // load pipeline matters more than operand reuse, and a second resident workgroup hides it
+    if (tiles256 < 4096) tiles256 = 0;
     if (geglu) {
         if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, true>(g, guard, stream);
         return launch_cfg<128, 128, 2, 2, 2, true>(g, guard, stream);
     }
-    if (maxN <= 64) return launch_cfg<64, 64, 2, 2, 3, false>(g, guard, stream);
+    if (maxN <= 64) return launch_cfg<64, 64, 2, 2, 5, false>(g, guard, stream);
     if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, false>(g, guard, stream);
     return launch_cfg<128, 128, 2, 2, 2, false>(g, guard, stream);
 }

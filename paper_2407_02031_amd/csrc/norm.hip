@@ -163,39 +163,48 @@ __global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* 
     }
 }
 
+// One wavefront per (sample, group): fixed-order sum of the chunk partials -> (mean, rstd).
+__global__ __launch_bounds__(64) void groupnorm_finalize_kernel(const uint16_t* __restrict__ x, const float* __restrict__ partials,
+                                                               float* __restrict__ stats, int T, int C, int groups, int nchunks, float eps) {
+    const int b = blockIdx.x / groups, g = blockIdx.x % groups;
+    const int lane = threadIdx.x;
+    const int cpg = C / groups;
+    float a1 = 0.f, a2 = 0.f;
+    for (int c = lane; c < nchunks; c += 64) {
+        const float* p = partials + (((size_t)b * nchunks + c) * groups + g) * 2;
+        a1 += p[0];
+        a2 += p[1];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) { a1 += __shfl_xor(a1, o, 64); a2 += __shfl_xor(a2, o, 64); }
+    if (lane == 0) {
+        const float n = (float)T * (float)cpg;
+        const float m1 = a1 / n;
+        const float var = fmaxf(a2 / n - m1 * m1, 0.f);
+        stats[2 * blockIdx.x] = bf16_to_f32(x[(size_t)b * T * C + g * cpg]) + m1;
+        stats[2 * blockIdx.x + 1] = rsqrtf(var + eps);
+    }
+}
+
 __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                        const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ beta,
-                                       const float* __restrict__ partials, int T, int C, int groups, int nchunks, float eps) {
-    extern __shared__ float sh[];   // [groups][2]: mean, rstd
+                                       const float* __restrict__ stats, int T, int C, int groups) {
     const int b = blockIdx.y, chunk = blockIdx.x;
     const int cp = threadIdx.x;
     const int cpg = C / groups;
     const int npairs = C >> 1;
+    if (cp >= npairs) return;
     const uint16_t* xb = x + (size_t)b * T * C;
     uint16_t* yb = y + (size_t)b * T * C;
-    if (cp < groups) {
-        float a1 = 0.f, a2 = 0.f;
-        for (int c = 0; c < nchunks; ++c) {
-            const float* p = partials + (((size_t)b * nchunks + c) * groups + cp) * 2;
-            a1 += p[0];
-            a2 += p[1];
-        }
-        const float n = (float)T * (float)cpg;
-        const float m1 = a1 / n;
-        const float var = fmaxf(a2 / n - m1 * m1, 0.f);
-        sh[2 * cp] = bf16_to_f32(xb[cp * cpg]) + m1;
-        sh[2 * cp + 1] = rsqrtf(var + eps);
-    }
-    __syncthreads();
-    if (cp >= npairs) return;
     const int g = (2 * cp) / cpg;
-    const float mean = sh[2 * g], rstd = sh[2 * g + 1];
+    const float mean = stats[2 * (b * groups + g)], rstd = stats[2 * (b * groups + g) + 1];
     const uint32_t gg = reinterpret_cast<const uint32_t*>(gamma)[cp];
     const uint32_t bb = reinterpret_cast<const uint32_t*>(beta)[cp];
     const float g0 = bf16lo_to_f32(gg) * rstd, g1 = bf16hi_to_f32(gg) * rstd;
     const float b0 = bf16lo_to_f32(bb), b1 = bf16hi_to_f32(bb);
     const int t0 = chunk * GN_TCHUNK;
     const int t1 = min(T, t0 + GN_TCHUNK);
+#pragma unroll 4
     for (int t = t0; t < t1; ++t) {
         const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
         const float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
@@ -206,7 +215,7 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
 
 size_t groupnorm_partials_bytes(int Bn, int T, int groups) {
     const size_t nchunks = (size_t)(T + GN_TCHUNK - 1) / GN_TCHUNK;
-    return (size_t)Bn * nchunks * groups * 2 * sizeof(float);
+    return round_up((size_t)Bn * nchunks * groups * 2 * sizeof(float), 256) + (size_t)Bn * groups * 2 * sizeof(float);
 }
 
 int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
@@ -222,8 +231,10 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
     dim3 grid(nchunks, Bn);
     hipLaunchKernelGGL(groupnorm_partial_kernel, grid, dim3(threads), (size_t)C * sizeof(float), stream, x, partials, T, C, groups, nchunks);
     SD_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, dim3(threads), (size_t)groups * 2 * sizeof(float), stream, x, y, gamma, beta,
-                       partials, T, C, groups, nchunks, eps);
+    float* stats = partials + round_up((size_t)Bn * nchunks * groups * 2 * sizeof(float), 256) / sizeof(float);
+    hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(Bn * groups), dim3(64), 0, stream, x, partials, stats, T, C, groups, nchunks, eps);
+    SD_HIP_CHECK(hipGetLastError());
+    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }

@@ -285,3 +285,31 @@ def test_patch_exact_integers(B):
     ref, _ = O.lora_patch(W, A, Bm, 2.0)
     assert np.array_equal(patched[0], ref)           # exactly representable -> identical bits
     assert np.array_equal(restored[0], W)
+
+
+# ------------------------------------------------------------------ HIP graph replay
+def test_stack_graph_replay_matches_eager(B):
+    """The stack call only enqueues kernels, so it can be captured into a HIP graph.  Every
+    replay, with eager work and synchronisations in between, must give the eager bits."""
+    import torch
+    cfg = small_cfg(T=200, depth=1)
+    p = G.make_stack_inputs(cfg, seed=2)
+    sp = B.StackParams(p)
+    x, ctx = dev(p["x"], B), dev(p["ctx"], B)
+    ws = torch.empty(B.spatial_transformer_workspace_bytes(cfg.Bn, cfg.T, cfg.C, cfg.Tc, cfg.Dc, sp.r_max), dtype=torch.uint8, device="cuda")
+    y_eager = B.spatial_transformer_fwd(x, ctx, sp, cfg.heads, ws=ws).clone()
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.spatial_transformer_fwd(x, ctx, sp, cfg.heads, out=y, ws=ws)
+    for i in range(4):
+        y.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager), f"replay {i} differs from the eager result"
+        # eager work between replays
+        again = B.spatial_transformer_fwd(x, ctx, sp, cfg.heads, ws=ws)
+        assert torch.equal(again, y_eager)
