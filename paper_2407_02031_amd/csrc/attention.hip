@@ -34,9 +34,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     // (sample, head, query tile) so that one head's K and V stay in one XCD's L2.
     const int total = gridDim.x;
     int wi = blockIdx.x;
-#ifndef EXP_NOREMAP
     if ((total & 7) == 0) wi = (wi & 7) * (total >> 3) + (wi >> 3);
-#endif
     const int qt = wi % qtiles;
     const int head = (wi / qtiles) % heads, b = wi / (qtiles * heads);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -170,26 +168,33 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             }
         }
     };
-    // p = exp2((s - m) * c) packed to bf16 in MFMA operand order, row sums into l
+    // p = exp2((s - m) * c) packed to bf16 in MFMA operand order; the row sum adds up the
+    // packed (rounded) values with a bf16 dot-product against ones, two per instruction, so
+    // the normaliser matches exactly what the second MFMA multiplies
     auto exponentials = [&](f32x16 (&s)[QB][2], bf16x8 (&pf)[QB][2][2]) {
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             const float mc = m[qb] * c;
-            float ls = 0.f;
+            float ls0 = 0.f, ls1 = 0.f;
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int g2 = 0; g2 < 2; ++g2) {
                     bf16x8 pk;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + e] * c - mc);
-                        ls += p;
-                        pk[e] = (__bf16)p;
+                    for (int e = 0; e < 4; ++e) {
+                        const float p0 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e] * c - mc);
+                        const float p1 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e + 1] * c - mc);
+                        const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
+                        pk[2 * e] = pp[0];
+                        pk[2 * e + 1] = pp[1];
+                        if (e & 1) ls1 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls1, false);
+                        else ls0 = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, ls0, false);
                     }
                     pf[qb][kb][g2] = pk;
                 }
-            l[qb] += ls;
+            l[qb] += ls0 + ls1;
         }
     };
     // O^T += V^T P^T.  k-slot j of sub-step (kb, g2) is key kb*32 + 16*g2 + 8*(j/4) + 4*hi + j%4,
@@ -219,52 +224,48 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         store_kv(1, 1);
     }
     __syncthreads();
-    f32x16 sc[QB][2], sn[QB][2];
-    compute_s(0, sc);
+    f32x16 sa[QB][2], sb[QB][2];
+    compute_s(0, sa);
 
     // ---- main loop, software-pipelined: the score MFMAs of tile t+1 are independent of the
     // exponentials of tile t and sit in the same basic block, so the matrix pipe and the
-    // vector ALU overlap inside one wavefront.  The last tile is peeled (nothing to prefetch,
-    // and it is the only one that may need masking).
+    // vector ALU overlap inside one wavefront.  Two tiles per trip (the score buffers swap
+    // roles), the last tile is peeled: nothing to prefetch, and only it may need masking.
     int vslot = 0;
     bf16x8 pf[QB][2][2];
-#pragma unroll 1
-    for (int t = 0; t + 1 < nt; ++t) {
-#ifdef EXP_NOLOAD
-        const bool pre = false;
-#else
+    // one pipelined step: finish tile t (scores in `cur`), start tile t+1 (scores into `nxt`)
+    auto step = [&](int t, f32x16 (&cur)[QB][2], f32x16 (&nxt)[QB][2]) {
         const bool pre = t + 2 < nt;
-#endif
         if (pre) load_kv(t + 2);
-#ifndef EXP_NOMAX
-        update_max(sc);
-#endif
-#ifndef EXP_NOS
-        compute_s(t + 1, sn);
-#endif
-#ifndef EXP_NOEXPS
-        exponentials(sc, pf);
-#endif
-#ifndef EXP_NOPV
+        update_max(cur);
+        compute_s(t + 1, nxt);
+        exponentials(cur, pf);
         accumulate_o(vslot, pf);
-#endif
-        // tile t+2: K slot t%2 was last read for S(t) one iteration ago, V slot (t+2)%3 for
+        // tile t+2: K slot t%2 was last read for S(t) one step ago, V slot (t+2)%3 for
         // tile t-1: both free since the previous barrier
         const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
         if (pre) store_kv(t & 1, vnext2);
         vslot = vslot == 2 ? 0 : vslot + 1;
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) sc[qb][kb] = sn[qb][kb];
-#ifndef EXP_NOBAR
         __syncthreads();
-#endif
+    };
+    int t = 0;
+#pragma unroll 1
+    for (; t + 2 < nt; t += 2) {
+        step(t, sa, sb);
+        step(t + 1, sb, sa);
     }
-    if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sc);
-    update_max(sc);
-    exponentials(sc, pf);
-    accumulate_o(vslot, pf);
+    if (t + 1 < nt) {            // one more pipelined step, last tile's scores end up in sb
+        step(t, sa, sb);
+        if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sb);
+        update_max(sb);
+        exponentials(sb, pf);
+        accumulate_o(vslot, pf);
+    } else {                     // last tile's scores are in sa
+        if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sa);
+        update_max(sa);
+        exponentials(sa, pf);
+        accumulate_o(vslot, pf);
+    }
 
     // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
 #pragma unroll

@@ -20,7 +20,13 @@
 
 namespace sd {
 
-__device__ __forceinline__ int swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }
+// XOR swizzle of the 16-byte chunk index inside an LDS row of CPR chunks (8: 128-byte rows,
+// 4: 64-byte rows): any 16 consecutive rows put the same logical chunk in 16 distinct
+// 16-byte slots of a 256-byte bank window.
+template <int CPR>
+__device__ __forceinline__ int swz(int row, int chunk) {
+    return CPR == 8 ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ ((row >> 2) & 3));
+}
 
 // erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7), far below bf16 resolution
 __device__ __forceinline__ float erf_as(float x) {
@@ -56,42 +62,64 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES>
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 constexpr int gemm_lds_chunks() {
-    constexpr int ring = STAGES * (BM + BN) * 8;
+    constexpr int ring = STAGES * (BM + BN) * (BK / 8);
     constexpr int epi = WGM * WGN * 32 * EPI_STRIDE / 4;
     return ring > epi ? ring : epi;
 }
 
 // GUARD: K segments that are not multiples of 64 (tail chunks read zeros).
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g) {
+// Two workgroups per CU whenever the ring leaves room for it (LDS <= 80 KB): the register
+// budget is then 256 per lane (accumulators in AGPRs, the rest in VGPRs).
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
+constexpr int gemm_min_waves() {
+    return gemm_lds_chunks<BM, BN, BK, WGM, WGN, STAGES>() * 16 <= 80 * 1024 ? 2 : 1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD>
+__global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WGN, STAGES>())) void gemm_kernel(const GemmGroup g) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
-    constexpr int NBLK = (BM + BN) / 8;        // 1 KB blocks (8 rows x 128 B) per stage
+    constexpr int CPR = BK / 8;                // 16-byte chunks per LDS row
+    constexpr int RPB = 64 / CPR;              // tile rows per 1 KB block (one wave-wide load)
+    constexpr int KK = BK / 16;                // MFMA k-steps per tile
+    constexpr int NBLK = (BM + BN) / RPB;      // 1 KB blocks per stage
     constexpr int LPT = NBLK / NW;             // direct-to-LDS loads per wave (= per lane) per tile
-    constexpr int STAGE = (BM + BN) * 8;       // 16-byte chunks per stage
+    constexpr int STAGE = (BM + BN) * CPR;     // 16-byte chunks per stage
+    static_assert(BK == 64 || BK == 32, "BK");
     constexpr int DIST = STAGES - 1;           // tiles in flight ahead of the one being multiplied
     static_assert(NBLK % NW == 0, "tile/waves mismatch");
     static_assert(!GEGLU || (NI % 2 == 0), "GEGLU needs value/gate column-block pairs per wave");
     static_assert(DIST >= 1 && DIST <= 4, "ring depth");
 
-    __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, WGM, WGN, STAGES>()];
+    __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, BK, WGM, WGN, STAGES>()];
 
     // ---- which problem, which tile ----
-    const int tile = blockIdx.x;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+    // contiguous range of tiles, and order tiles inside a problem in bands of 8 row-tiles
+    // (row-tile index fastest), so that the workgroups resident on one XCD share a small set
+    // of activation rows and weight rows.
+    int tile = blockIdx.x;
+    {
+        const int total = gridDim.x;
+        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
+    }
     int pi = 0;
 #pragma unroll 1
     for (int i = 1; i < g.n; ++i)
         if (tile >= g.p[i].tile_begin) pi = i;
     const GemmProblem& P = g.p[pi];
     const int local = tile - P.tile_begin;
-    const int tn = local % P.tiles_n, tm = local / P.tiles_n;
+    const int band_tiles = 8 * P.tiles_n;
+    const int band = local / band_tiles, rem = local - band * band_tiles;
+    const int band_rows = min(8, P.tiles_m - band * 8);
+    const int tn = rem / band_rows, tm = band * 8 + rem % band_rows;
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
     const int m0 = tm * BM, n0 = tn * BN_OUT;
     const int Mp = P.Mp, N = P.N, K0 = P.K0, K1 = P.K1;
-    const int nk0 = (K0 + 63) >> 6, nk1 = (K1 + 63) >> 6, nkt = nk0 + nk1;
+    const int nk0 = (K0 + BK - 1) / BK, nk1 = (K1 + BK - 1) / BK, nkt = nk0 + nk1;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -112,39 +140,46 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
         }
     };
 
-    // ---- loader.  Load j of wave w fills 1 KB block (j*NW + w) of a stage: 8 tile rows
-    // (P rows first, then Q rows) of 8 chunks; lane l lands at chunk position l&7 of row
-    // l>>3, so it must fetch the logical chunk that the XOR swizzle places there.
-    const uint16_t* gp[LPT];     // this lane's source (row start + chunk) per load, current segment
-    int kcol[LPT];               // first k of that chunk within a 64-deep tile
-    auto setup = [&](int seg) {
-        const uint16_t* pbase = seg ? P.p1 : P.p0;
-        const uint16_t* qbase = seg ? P.q1 : P.q0;
-        const int64_t ldp = seg ? P.ldp1 : P.ldp0, ldq = seg ? P.ldq1 : P.ldq0;
+    // ---- loader.  Load j of wave w fills 1 KB block (j*NW + w) of a stage: RPB tile rows
+    // (P rows first, then Q rows) of CPR chunks; lane l lands at chunk position l % CPR of row
+    // l / CPR, so it must fetch the logical chunk that the XOR swizzle places there.
+    const uint16_t* gp0[LPT];    // this lane's source (row start + chunk) per load, K segment 0
+    const uint16_t* gp1[LPT];    // ... K segment 1 (LoRA); equals gp0 when there is none
+    int kcol[LPT];               // first k of that chunk within a tile
+    {
+        const uint16_t* p0 = P.p0; const uint16_t* q0 = P.q0;
+        const uint16_t* p1 = K1 ? P.p1 : P.p0; const uint16_t* q1 = K1 ? P.q1 : P.q0;
+        const int64_t ldp0 = P.ldp0, ldq0 = P.ldq0;
+        const int64_t ldp1 = K1 ? P.ldp1 : P.ldp0, ldq1 = K1 ? P.ldq1 : P.ldq0;
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-            const int row = (j * NW + wave) * 8 + (lane >> 3);     // row within the stage
-            const int c = (lane & 7) ^ ((row >> 1) & 7);           // logical chunk fetched by this lane
+            const int row = (j * NW + wave) * RPB + lane / CPR;    // row within the stage
+            const int c = swz<CPR>(row, lane % CPR);               // logical chunk fetched by this lane
             kcol[j] = c * 8;
             if (row < BM) {
                 int r = m0 + row;
                 r = r < Mp ? r : Mp - 1;
-                gp[j] = pbase + (int64_t)r * ldp + c * 8;
+                gp0[j] = p0 + (int64_t)r * ldp0 + c * 8;
+                gp1[j] = p1 + (int64_t)r * ldp1 + c * 8;
             } else {
-                gp[j] = qbase + (int64_t)qrow(row - BM) * ldq + c * 8;
+                const int qr = qrow(row - BM);
+                gp0[j] = q0 + (int64_t)qr * ldq0 + c * 8;
+                gp1[j] = q1 + (int64_t)qr * ldq1 + c * 8;
             }
         }
-    };
+    }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-    auto issue_tile = [&](int t) {
-        if (t == nk0) setup(1);
-        const int kt = t < nk0 ? t : t - nk0;
-        const int Kseg = t < nk0 ? K0 : K1;
-        const int kb = kt * 64;
-        const uint32_t sbase = lds_base + (uint32_t)(t % STAGES) * (STAGE * 16) + (uint32_t)wave * 1024;
+    const uint32_t wave_base = lds_base + (uint32_t)wave * 1024;
+    // issue the loads of k-step t into ring stage `stg` (branch-free: both segments' pointers
+    // are precomputed, the step picks one)
+    auto issue_tile = [&](int t, int stg) {
+        const bool s1 = t >= nk0;
+        const int kb = (s1 ? t - nk0 : t) * BK;
+        const int Kseg = s1 ? K1 : K0;
+        const uint32_t sbase = wave_base + (uint32_t)stg * (STAGE * 16);
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
-            const void* src = gp[j] + kb;
+            const void* src = (s1 ? gp1[j] : gp0[j]) + kb;
             if (GUARD) src = (kb + kcol[j] < Kseg) ? src : (const void*)g_gemm_zeros;
             dma16(src, sbase + (uint32_t)j * (NW * 1024));
         }
@@ -158,63 +193,71 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    // one 64-deep tile out of ring stage `st`; fragments of k-step kk+1 are fetched while
+    // one BK-deep tile out of ring stage `st`; fragments of k-step kk+1 are fetched while
     // the MFMAs of k-step kk execute
     auto compute = [&](int st) {
         const u32x4* la = lds + st * STAGE;
-        const u32x4* lb = la + BM * 8;
+        const u32x4* lb = la + BM * CPR;
         bf16x8 af[2][MI], bfr[2][NI];
         auto fetch = [&](int kk, int fs) {
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 const int r = wm + mi * 32 + l32;
-                af[fs][mi] = __builtin_bit_cast(bf16x8, la[r * 8 + swz(r, kk * 2 + hi)]);
+                af[fs][mi] = __builtin_bit_cast(bf16x8, la[r * CPR + swz<CPR>(r, kk * 2 + hi)]);
             }
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni) {
                 const int r = wn + ni * 32 + l32;
-                bfr[fs][ni] = __builtin_bit_cast(bf16x8, lb[r * 8 + swz(r, kk * 2 + hi)]);
+                bfr[fs][ni] = __builtin_bit_cast(bf16x8, lb[r * CPR + swz<CPR>(r, kk * 2 + hi)]);
             }
         };
         fetch(0, 0);
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < 3) fetch(kk + 1, (kk + 1) & 1);
+        for (int kk = 0; kk < KK; ++kk) {
+            if (kk + 1 < KK) fetch(kk + 1, (kk + 1) & 1);
+            // keep the reads of k-step kk+1 ahead of the MFMAs of k-step kk: left alone, the
+            // scheduler sinks them to just before their use and exposes the LDS latency
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NI; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][mi], bfr[kk & 1][ni], acc[mi][ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     // ---- prologue: the first DIST tiles in flight
-    setup(0);
 #pragma unroll
     for (int d = 0; d < DIST; ++d)
-        if (d < nkt) issue_tile(d);
+        if (d < nkt) issue_tile(d, d);
 
     // ---- main loop.  Step t: wait until this wave's loads of tile t have landed (loads of
     // newer tiles may stay in flight), barrier (every wave's part of tile t is in LDS and
     // every wave is done reading the stage of tile t-1), refill that stage with tile t+DIST,
-    // multiply tile t.
-    int st = 0;
+    // multiply tile t.  The steady-state loop has no conditionals; the last DIST steps run
+    // in a second loop with the shrinking wait counts.
+    int st = 0;                         // stage of tile t
+    int sf = DIST;                      // stage to refill (= stage of tile t-1)
+    int t = 0;
 #pragma unroll 1
-    for (int t = 0; t < nkt; ++t) {
-        {   // newer tiles already issued: min(DIST - 1, nkt - 1 - t)
-            const int newer = nkt - 1 - t;
-            if (DIST >= 4 && newer >= 3) wait_vmcnt<3 * LPT>();
-            else if (DIST >= 3 && newer >= 2) wait_vmcnt<2 * LPT>();
-            else if (DIST >= 2 && newer >= 1) wait_vmcnt<LPT>();
-            else wait_vmcnt<0>();
-        }
+    for (; t + DIST < nkt; ++t) {
+        wait_vmcnt<(DIST - 1) * LPT>();
         __syncthreads();
-#ifndef EXP_NOLOAD
-        if (t + DIST < nkt) issue_tile(t + DIST);
-#endif
-#ifndef EXP_NOCOMPUTE
+        issue_tile(t + DIST, sf);
         compute(st);
-#endif
+        sf = st;
+        st = st + 1 == STAGES ? 0 : st + 1;
+    }
+#pragma unroll 1
+    for (; t < nkt; ++t) {
+        const int newer = nkt - 1 - t;  // tiles issued after tile t
+        if (DIST >= 4 && newer >= 3) wait_vmcnt<3 * LPT>();
+        else if (DIST >= 3 && newer >= 2) wait_vmcnt<2 * LPT>();
+        else if (DIST >= 2 && newer >= 1) wait_vmcnt<LPT>();
+        else wait_vmcnt<0>();
+        __syncthreads();
+        compute(st);
         st = st + 1 == STAGES ? 0 : st + 1;
     }
     __syncthreads();   // ring reads done before the epilogue reuses LDS
@@ -313,7 +356,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_kernel(const GemmGroup g)
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int STAGES, bool GEGLU>
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU>
 static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
     int total = 0;
@@ -327,9 +370,9 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     g.total_tiles = total;
     if (total == 0) return SD_OK;
     if (guard)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, GEGLU, true>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, true>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
     else
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, WGM, WGN, STAGES, GEGLU, false>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, false>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
@@ -360,16 +403,15 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (g.p[i].Mp > 0 && g.p[i].N > 0) { if (w != i) g.p[w] = g.p[i]; ++w; }
     g.n = w;
     if (w == 0) return SD_OK;
-    // 128x128 tiles, two workgroups per CU: with K of a few hundred the fill latency of the
-    // load pipeline matters more than operand reuse, and a second resident workgroup hides it
-    if (tiles256 < 4096) tiles256 = 0;
-    if (geglu) {
-        if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, true>(g, guard, stream);
-        return launch_cfg<128, 128, 2, 2, 2, true>(g, guard, stream);
-    }
-    if (maxN <= 64) return launch_cfg<64, 64, 2, 2, 5, false>(g, guard, stream);
-    if (tiles256 >= 512) return launch_cfg<256, 128, 2, 2, 3, false>(g, guard, stream);
-    return launch_cfg<128, 128, 2, 2, 2, false>(g, guard, stream);
+    // Tile choice.  Measured on MI355X the operand stream (direct-to-LDS loads out of L2) and
+    // not the MFMA rate bounds these GEMMs; 128x128x64 tiles with a 2-stage ring (64 KB, two
+    // workgroups per CU so one workgroup's prologue and epilogue overlap the other's main
+    // loop) beat 256x128 tiles at every shape of the transformer block.  Down-projections
+    // (N = rank <= 64) use 64x64 tiles with a 5-stage ring.
+    (void)tiles256;
+    if (geglu) return launch_cfg<128, 128, 64, 2, 2, 2, true>(g, guard, stream);
+    if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false>(g, guard, stream);
+    return launch_cfg<128, 128, 64, 2, 2, 2, false>(g, guard, stream);
 }
 
 }  // namespace sd
