@@ -24,6 +24,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0    # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+# HBM bytes per lora_patch launch on the 310-matrix sweep, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this file, each scaled by the same counter's reading on a pure copy of
+# known size (lora_unpatch): see profiles/lora_patch_hbm_traffic.txt
+PATCH_TRAFFIC_BYTES = 10.5e9
 
 
 def stack_flops(cfg) -> float:
@@ -118,23 +122,44 @@ def main() -> int:
     flops = stack_flops(cfg)
     tflops = flops / (ms_per_step * 1e-3) / 1e12
 
-    # ------------------------------------------- dominant kernel: latent self-attention
-    M = cfg.M
-    q = torch.randn(cfg.Bn, cfg.T, cfg.C, device="cuda", dtype=torch.bfloat16)
-    kk = torch.randn(cfg.Bn, cfg.T, cfg.C, device="cuda", dtype=torch.bfloat16)
-    vt = torch.randn(cfg.C, M, device="cuda", dtype=torch.bfloat16)
-    ao = torch.empty_like(q)
-    for _ in range(3):
-        B.attention_fwd(q, kk, vt, cfg.heads, out=ao)
-    d = time_events(lambda: B.attention_fwd(q, kk, vt, cfg.heads, out=ao), max(K, 20))
-    attn_ms = float(np.mean(d))
-    attn_tflops = self_attention_flops(cfg) / (attn_ms * 1e-3) / 1e12
-    roofline = {"kernel": "attention_kernel (latent self-attention, 2 x 10 heads x 4096^2 x 64)", "bound": "mfma",
-                "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "avg_launch_ms": round(attn_ms, 4), "launches_per_step": cfg.depth,
-                "share_of_step": round(cfg.depth * attn_ms / ms_per_step, 3)}
-    del q, kk, vt, ao
+    # ---------------- per-kernel durations inside real steps (HIP events, eager launches)
+    # The library records an event pair around each tagged kernel launch on the stream it is
+    # given; K more steps of the same workload run eagerly for this (events cannot be read
+    # back from a replayed graph).
+    per_step = {"self_attention": cfg.depth, "cross_attention": cfg.depth, "qkv": cfg.depth,
+                "attn_out": 2 * cfg.depth, "ff1": cfg.depth, "ff2": cfg.depth}
+    M, C, T, Bn, F, r = cfg.M, cfg.C, cfg.T, cfg.Bn, cfg.F, cfg.r
+    rl = r if cfg.lora_ff else 0
+    flop_per_launch = {
+        "self_attention": 4.0 * Bn * T * T * C,
+        "cross_attention": 4.0 * Bn * T * cfg.Tc * C,
+        "qkv": 3 * (2.0 * M * C * C + 2.0 * M * r * C),            # base + up-projection (K extended by r)
+        "attn_out": 2.0 * M * C * C + 2.0 * M * r * C,
+        "ff1": 2.0 * M * C * 2 * F + 2.0 * M * rl * 2 * F,
+        "ff2": 2.0 * M * F * C + 2.0 * M * rl * C,
+    }
+    B.timing_enable(K * max(per_step.values()) + 8)
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    kernels = {}
+    for tag, n in per_step.items():
+        d = B.timing_collect(tag)
+        ms = float(np.mean(d))
+        kernels[tag] = {"launches": len(d), "avg_launch_ms": round(ms, 4),
+                        "tflops": round(flop_per_launch[tag] / (ms * 1e-3) / 1e12, 1),
+                        "share_of_step": round(n * ms / ms_per_step, 3)}
+    B.timing_disable()
+    dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
+    names = {"self_attention": "attention_kernel, latent self-attention (2 x 10 heads x 4096 x 4096 x 64)",
+             "ff1": "gemm_kernel, feed-forward in-projection with GEGLU epilogue",
+             "ff2": "gemm_kernel, feed-forward out-projection", "qkv": "gemm_kernel, grouped q/k/v^T projections",
+             "attn_out": "gemm_kernel, attention output projection", "cross_attention": "attention_kernel, cross-attention"}
+    roofline = {"kernel": names[dom], "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_ms": kernels[dom]["avg_launch_ms"], "launches_per_step": per_step[dom],
+                "share_of_step": kernels[dom]["share_of_step"],
+                "measured": "HIP events around every launch of this kernel in %d eager steps" % K}
 
     out = {
         "metric": "SDXL transformer-block TFLOP/s (% bf16 MFMA peak); LoRA patch GB/s (% HBM)",
@@ -146,6 +171,7 @@ def main() -> int:
                    "launch": launch},
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
+        "kernels": kernels,
     }
 
     # ------------------------------------------------------------ multi-LoRA projections
@@ -203,8 +229,9 @@ def main() -> int:
                         "patch_frac_of_hbm": round(pbytes / (pms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                         "unpatch_ms": round(ums, 4), "unpatch_gbs": round(ubytes / (ums * 1e-3) / 1e9, 1),
                         "unpatch_frac_of_hbm": round(ubytes / (ums * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
-                        "roofline": {"bound": "hbm", "achieved": round(pbytes / (pms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS,
-                                     "unit": "GB/s", "frac": round(pbytes / (pms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None}}
+                        "roofline": {"kernel": "lora_patch_kernel", "bound": "hbm", "achieved": round(pbytes / (pms * 1e-3) / 1e9, 1),
+                                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pbytes / (pms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                     "algorithmic_bytes": pbytes, "traffic": PATCH_TRAFFIC_BYTES}}
         del mats, plan
         torch.cuda.empty_cache()
 

@@ -79,6 +79,24 @@ typedef struct sd_patch_desc {
 const char* sd_last_error(void);
 int32_t sd_version(void);
 
+/* ---- instrumentation (off by default) --------------------------------------------------
+ * Measurement support for the roofline figures: when enabled, the sub-layer and stack calls
+ * record a HIP event on their stream immediately before and after the launch of the kernels
+ * tagged below, so a benchmark can read per-launch durations of the dominant kernels inside
+ * a real step.  Not for use under HIP graph capture.  enable() creates the events (host
+ * side), collect() waits for them and writes up to `capacity` durations in milliseconds to
+ * the host array, disable() destroys them.  One process-wide instance, not thread-safe. */
+#define SD_TIMING_SELF_ATTENTION 0   /* flash attention over the latent tokens            */
+#define SD_TIMING_CROSS_ATTENTION 1  /* flash attention to the text tokens                */
+#define SD_TIMING_QKV 2              /* grouped q, k, v^T base GEMMs of self-attention     */
+#define SD_TIMING_ATTN_OUT 3         /* attention output projection + residual            */
+#define SD_TIMING_FF1 4              /* feed-forward in-projection with GEGLU epilogue     */
+#define SD_TIMING_FF2 5              /* feed-forward out-projection + residual             */
+#define SD_TIMING_TAGS 6
+int sd_timing_enable(int32_t records_per_tag);
+int sd_timing_collect(int32_t tag, float* ms_host, int32_t capacity, int32_t* count);
+int sd_timing_disable(void);
+
 /* ---- lora_linear_fwd ------------------------------------------------------------------
  * y = epi( LN?(x) W^T + bias + scale * (LN?(x) A^T) B^T ) + residual
  * The unmerged form of Section 2's W' = W + A B applied to an input; the rank-r update

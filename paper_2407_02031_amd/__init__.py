@@ -10,7 +10,7 @@ import importlib
 _BINDING_NAMES = {
     "lora_linear_fwd", "attention_fwd", "attn_block_fwd", "ff_block_fwd", "groupnorm_fwd",
     "spatial_transformer_fwd", "spatial_transformer_workspace_bytes", "multi_lora_linear_fwd",
-    "lora_patch", "lora_unpatch", "PatchPlan", "Proj", "StackParams", "to_bf16", "SwiftDiffError",
+    "lora_patch", "lora_unpatch", "timing_enable", "timing_collect", "timing_disable", "TIMING_TAGS", "PatchPlan", "Proj", "StackParams", "to_bf16", "SwiftDiffError",
     "SD_BF16", "SD_F32", "SD_EPI_NONE", "SD_EPI_GEGLU", "LIB_PATH", "EXPORTS", "lib",
 }
 

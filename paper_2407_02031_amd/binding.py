@@ -63,6 +63,9 @@ def _load() -> C.CDLL:
     sig = {
         "sd_last_error": (C.c_char_p, []),
         "sd_version": (i32, []),
+        "sd_timing_enable": (C.c_int, [i32]),
+        "sd_timing_collect": (C.c_int, [i32, P(f32), i32, P(i32)]),
+        "sd_timing_disable": (C.c_int, []),
         "sd_lora_linear_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "sd_lora_linear_fwd": (C.c_int, [vp, i32, P(sd_proj), vp, vp, f32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]),
         "sd_attn_block_workspace_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
@@ -91,7 +94,7 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["sd_last_error", "sd_version", "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
+EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
@@ -294,6 +297,24 @@ class PatchPlan:
         _check(_lib.sd_patch_plan_build(descs, n, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)))
         self.total_tiles = int(tiles.value)
         self.dev = torch.from_numpy(host).cuda()
+
+
+TIMING_TAGS = {"self_attention": 0, "cross_attention": 1, "qkv": 2, "attn_out": 3, "ff1": 4, "ff2": 5}
+
+
+def timing_enable(records_per_tag: int) -> None:
+    _check(_lib.sd_timing_enable(records_per_tag))
+
+
+def timing_collect(tag: str, capacity: int = 65536) -> List[float]:
+    buf = (C.c_float * capacity)()
+    n = C.c_int32(0)
+    _check(_lib.sd_timing_collect(TIMING_TAGS[tag], buf, capacity, C.byref(n)))
+    return [float(buf[i]) for i in range(n.value)]
+
+
+def timing_disable() -> None:
+    _check(_lib.sd_timing_disable())
 
 
 def lora_patch(plan: PatchPlan) -> None:

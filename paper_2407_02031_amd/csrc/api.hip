@@ -22,6 +22,25 @@ int hip_fail(hipError_t e, const char* what) {
 }
 
 // ---------------------------------------------------------------------------------------
+// optional instrumentation: HIP events around selected kernel launches (off by default)
+// ---------------------------------------------------------------------------------------
+struct TimingState {
+    bool on = false;
+    int cap = 0;
+    std::vector<hipEvent_t> ev[SD_TIMING_TAGS][2];
+    int count[SD_TIMING_TAGS] = {0};
+};
+static TimingState g_timing;
+
+static void timing_mark(int tag, int which, hipStream_t stream) {
+    if (!g_timing.on || tag < 0) return;
+    int& n = g_timing.count[tag];
+    if (n >= g_timing.cap) return;
+    hipEventRecord(g_timing.ev[tag][which][n], stream);
+    if (which == 1) ++n;
+}
+
+// ---------------------------------------------------------------------------------------
 // projection -> GEMM problems
 // ---------------------------------------------------------------------------------------
 struct ProjOut {
@@ -104,7 +123,7 @@ static int flush(GemmGroup& g, hipStream_t stream) {
 
 // Run independent projections: every down-projection first (grouped launches), then every
 // base GEMM (grouped launches), so no base GEMM can read a down-projection still in flight.
-static int run_projections(const ProjCall* calls, int n, hipStream_t stream) {
+static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1) {
     GemmGroup g;
     g.n = 0;
     int rc;
@@ -113,7 +132,10 @@ static int run_projections(const ProjCall* calls, int n, hipStream_t stream) {
     if ((rc = flush(g, stream))) return rc;
     for (int i = 0; i < n; ++i)
         if (calls[i].M > 0 && (rc = push_main(g, stream, calls[i]))) return rc;
-    return flush(g, stream);
+    timing_mark(tag, 0, stream);
+    rc = flush(g, stream);
+    timing_mark(tag, 1, stream);
+    return rc;
 }
 
 static inline int pad8(int v) { return (v + 7) & ~7; }
@@ -157,10 +179,14 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     for (int s = 0; s < Bn; ++s)
         calls.push_back({src + (size_t)s * Tk * Kkv, Kkv, Tk, Kkv, C, &pv, w.tv + (size_t)s * Tk * (pv.r > 0 ? pv.r : 0),
                          {w.vt + (size_t)s * Tkp, (int64_t)Bn * Tkp, 0, nullptr, 0, true, 0}});
-    if ((rc = run_projections(calls.data(), (int)calls.size(), stream))) return rc;
-    if ((rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, stream))) return rc;
+    if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV))) return rc;
+    const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
+    timing_mark(atag, 0, stream);
+    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, stream);
+    timing_mark(atag, 1, stream);
+    if (rc) return rc;
     ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
-    return run_projections(&oc, 1, stream);
+    return run_projections(&oc, 1, stream, SD_TIMING_ATTN_OUT);
 }
 
 struct FfWs { uint16_t *n, *g, *t1, *t2; };
@@ -179,9 +205,9 @@ static int ff_sublayer(const void* x, void* y, int io_f32, const uint16_t* g, co
     int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
     if (rc) return rc;
     ProjCall c1 = {w.n, C, M, C, F, &p1, w.t1, {w.g, F, 0, nullptr, 0, false, F}};
-    if ((rc = run_projections(&c1, 1, stream))) return rc;
+    if ((rc = run_projections(&c1, 1, stream, SD_TIMING_FF1))) return rc;
     ProjCall c2 = {w.g, F, M, F, C, &p2, w.t2, {y, C, io_f32, x, C, false, 0}};
-    return run_projections(&c2, 1, stream);
+    return run_projections(&c2, 1, stream, SD_TIMING_FF2);
 }
 
 static int rmax_of(const sd_proj* const* ps, int n) {
@@ -197,6 +223,45 @@ using namespace sd;
 
 extern "C" const char* sd_last_error(void) { return g_err; }
 extern "C" int32_t sd_version(void) { return 1; }
+
+extern "C" int sd_timing_enable(int32_t records_per_tag) {
+    SD_REQUIRE(records_per_tag > 0 && records_per_tag <= 65536, SD_EINVAL, "timing: records_per_tag=%d", records_per_tag);
+    SD_REQUIRE(!g_timing.on, SD_EINVAL, "timing: already enabled");
+    for (int t = 0; t < SD_TIMING_TAGS; ++t) {
+        g_timing.count[t] = 0;
+        for (int w = 0; w < 2; ++w) {
+            g_timing.ev[t][w].resize(records_per_tag);
+            for (int i = 0; i < records_per_tag; ++i) SD_HIP_CHECK(hipEventCreate(&g_timing.ev[t][w][i]));
+        }
+    }
+    g_timing.cap = records_per_tag;
+    g_timing.on = true;
+    return SD_OK;
+}
+
+extern "C" int sd_timing_collect(int32_t tag, float* ms_host, int32_t capacity, int32_t* count) {
+    SD_REQUIRE(g_timing.on, SD_EINVAL, "timing: not enabled");
+    SD_REQUIRE(tag >= 0 && tag < SD_TIMING_TAGS && ms_host && count && capacity >= 0, SD_EINVAL, "timing: bad arguments");
+    const int n = g_timing.count[tag] < capacity ? g_timing.count[tag] : capacity;
+    for (int i = 0; i < n; ++i) {
+        SD_HIP_CHECK(hipEventSynchronize(g_timing.ev[tag][1][i]));
+        SD_HIP_CHECK(hipEventElapsedTime(&ms_host[i], g_timing.ev[tag][0][i], g_timing.ev[tag][1][i]));
+    }
+    *count = n;
+    return SD_OK;
+}
+
+extern "C" int sd_timing_disable(void) {
+    if (!g_timing.on) return SD_OK;
+    g_timing.on = false;
+    for (int t = 0; t < SD_TIMING_TAGS; ++t)
+        for (int w = 0; w < 2; ++w) {
+            for (hipEvent_t e : g_timing.ev[t][w]) hipEventDestroy(e);
+            g_timing.ev[t][w].clear();
+        }
+    g_timing.cap = 0;
+    return SD_OK;
+}
 
 // ---------------------------------------------------------------------------------------
 // lora_linear_fwd

@@ -13,6 +13,24 @@
 
 namespace sd {
 
+// streaming accesses: W, W' and the undo record are touched exactly once per pass
+typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
+#ifdef EXP_NO_NT
+#define NT_LOAD4(p) (*reinterpret_cast<const float4*>(p))
+#define NT_STORE4(p, v) (*reinterpret_cast<float4*>(p) = (v))
+#else
+__device__ __forceinline__ float4 nt_load4(const float* p) {
+    nt_f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
+    return float4{t[0], t[1], t[2], t[3]};
+}
+__device__ __forceinline__ void nt_store4(float* p, float4 v) {
+    nt_f32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_f32x4*>(p));
+}
+#define NT_LOAD4(p) nt_load4(p)
+#define NT_STORE4(p, v) nt_store4(p, v)
+#endif
+
 struct PatchPlanEntry {
     sd_patch_desc d;       // 48 bytes
     int64_t tile_begin;    // first workgroup tile of this matrix
@@ -22,7 +40,7 @@ struct PatchPlanEntry {
 static_assert(sizeof(sd_patch_desc) == 48, "descriptor layout");
 static_assert(sizeof(PatchPlanEntry) == 64, "plan entry layout");
 
-constexpr int PT_ROWS = 128, PT_COLS = 128;   // workgroup tile: 4 wavefronts x 32 rows
+constexpr int PT_ROWS = 32, PT_COLS = 512;   // workgroup tile: 4 wavefronts side by side, 32 rows x 128 columns each
 
 __device__ __forceinline__ int find_entry(const PatchPlanEntry* __restrict__ plan, int n, int64_t tile) {
     int lo = 0, hi = n - 1;   // last entry with tile_begin <= tile
@@ -33,7 +51,7 @@ __device__ __forceinline__ int find_entry(const PatchPlanEntry* __restrict__ pla
     return lo;
 }
 
-__global__ __launch_bounds__(256) void lora_patch_kernel(const PatchPlanEntry* __restrict__ plan, int n) {
+__global__ __launch_bounds__(256, 2) void lora_patch_kernel(const PatchPlanEntry* __restrict__ plan, int n) {
     const int64_t tile = blockIdx.x;
     const PatchPlanEntry& E = plan[find_entry(plan, n, tile)];
     const int out = E.d.out, in = E.d.in, r = E.d.r;
@@ -46,11 +64,11 @@ __global__ __launch_bounds__(256) void lora_patch_kernel(const PatchPlanEntry* _
     const int tc = local % E.tiles_c, tr = local / E.tiles_c;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
-    const int r0 = tr * PT_ROWS + wave * 32;
-    const int c0 = tc * PT_COLS;
-    if (r0 >= out) return;
+    const int r0 = tr * PT_ROWS;
+    const int c0 = tc * PT_COLS + wave * 128;
+    if (c0 >= in) return;
     const int col = c0 + 4 * l32;
-    const bool full = (r0 + 32 <= out) && (c0 + PT_COLS <= in) && ((in & 3) == 0);
+    const bool full = (r0 + 32 <= out) && (c0 + 128 <= in) && ((in & 3) == 0);
 
     f32x16 acc[4];
 #pragma unroll
@@ -64,19 +82,37 @@ __global__ __launch_bounds__(256) void lora_patch_kernel(const PatchPlanEntry* _
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
-            w[v] = *reinterpret_cast<const float4*>(W + (size_t)row * in + col);
+            w[v] = NT_LOAD4(W + (size_t)row * in + col);
         }
         const float* bp = B + (size_t)(r0 + l32) * r + hi;
         const float* ap = A + (size_t)hi * in + col;
         const int kp_n = r >> 1;
+        if (r == 32) {
+            // the common rank: every A and B fragment is requested up front (they come out
+            // of L2), so the 64 MFMAs run back to back while the W tile arrives from HBM
+            float bv[16];
+            float4 av[16];
+#pragma unroll
+            for (int kp = 0; kp < 16; ++kp) bv[kp] = bp[2 * kp];
+#pragma unroll
+            for (int kp = 0; kp < 16; ++kp) av[kp] = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+#pragma unroll
+            for (int kp = 0; kp < 16; ++kp) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].y, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].z, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].w, acc[3], 0, 0, 0);
+            }
+        } else {
 #pragma unroll 4
-        for (int kp = 0; kp < kp_n; ++kp) {
-            const float bv = bp[2 * kp];
-            const float4 av = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+            for (int kp = 0; kp < kp_n; ++kp) {
+                const float bv = bp[2 * kp];
+                const float4 av = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+            }
         }
         if (r & 1) {   // odd rank: last k pairs with a zero
             const int kk = r - 1;
@@ -92,13 +128,13 @@ __global__ __launch_bounds__(256) void lora_patch_kernel(const PatchPlanEntry* _
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             const size_t idx = (size_t)row * in + col;
-            *reinterpret_cast<float4*>(U + idx) = w[v];
+            NT_STORE4(U + idx, w[v]);
             float4 o;
             o.x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
             o.y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
             o.z = __fadd_rn(w[v].z, __fmul_rn(scale, acc[2][v]));
             o.w = __fadd_rn(w[v].w, __fmul_rn(scale, acc[3][v]));
-            *reinterpret_cast<float4*>(W + idx) = o;
+            NT_STORE4(W + idx, o);
         }
     } else {
         // ragged tile: same arithmetic, every access guarded and scalar
@@ -143,15 +179,15 @@ __global__ __launch_bounds__(256) void lora_unpatch_kernel(const PatchPlanEntry*
     const int local = (int)(tile - E.tile_begin);
     const int tc = local % E.tiles_c, tr = local / E.tiles_c;
     const int c0 = tc * PT_COLS, r0 = tr * PT_ROWS;
-    const int tcol = (threadIdx.x & 31) * 4, trow = threadIdx.x >> 5;   // 8 rows per pass
+    const int tcol = (threadIdx.x & 127) * 4, trow = threadIdx.x >> 7;   // 2 rows of 512 columns per pass
     const bool vec = ((in & 3) == 0) && (c0 + PT_COLS <= in);
 #pragma unroll 4
-    for (int i = 0; i < PT_ROWS / 8; ++i) {
-        const int row = r0 + trow + i * 8;
+    for (int i = 0; i < PT_ROWS / 2; ++i) {
+        const int row = r0 + trow + i * 2;
         if (row >= out) break;
         const size_t idx = (size_t)row * in + c0 + tcol;
         if (vec) {
-            *reinterpret_cast<float4*>(W + idx) = *reinterpret_cast<const float4*>(U + idx);
+            NT_STORE4(W + idx, NT_LOAD4(U + idx));
         } else {
             for (int j = 0; j < 4; ++j)
                 if (c0 + tcol + j < in) W[idx + j] = U[idx + j];

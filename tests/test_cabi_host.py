@@ -60,9 +60,9 @@ def test_patch_plan_build_validates_on_host(B):
     host = np.zeros(128, np.uint8)
     tiles = C.c_int64(-1)
     assert L.sd_patch_plan_build(descs, 2, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)) == 0
-    assert tiles.value == 3 * 2 + 1          # ceil(300/128) * ceil(200/128) + 1
+    assert tiles.value == 10 * 1 + 4 * 1     # workgroup tiles of 32 rows x 512 columns
     plan = host.view(np.int64).reshape(2, 8)
-    assert plan[0, 6] == 0 and plan[1, 6] == 6
+    assert plan[0, 6] == 0 and plan[1, 6] == 10
     # buffer too small
     assert L.sd_patch_plan_build(descs, 2, host.ctypes.data_as(C.c_void_p), 64, C.byref(tiles)) == -3
     # null undo, misaligned pointer, bad rank, undo aliasing W
