@@ -8,15 +8,13 @@
 //
 // Tiling: BM x BN output tile per workgroup, BK = 64, WGM x WGN wavefronts, each owning
 // (BM/WGM) x (BN/WGN) as 32x32x16 bf16 MFMA tiles with fp32 accumulators.
-// Pipeline: operand tiles go global -> registers -> LDS (16-byte chunks, XOR-swizzled so
-// the 32 rows one MFMA operand read touches fall in distinct banks).  Two register sets
-// keep the loads of tiles t+1 and t+2 in flight while tile t is multiplied out of a
-// two-deep LDS ring; inside a tile the operand fragments of k-step kk+1 are read from LDS
-// while the MFMAs of k-step kk run.  The epilogue stages each 32-row block of a wave's
+// Pipeline: operand tiles go global -> LDS directly (wave-wide 1 KB loads of 16-byte
+// chunks, XOR-swizzled so the 32 rows one MFMA operand read touches fall in distinct
+// banks) into a ring of STAGES tiles, STAGES-1 of them in flight ahead of the one being
+// multiplied; inside a tile the operand fragments of k-step kk+1 are read from LDS while
+// the MFMAs of k-step kk run.  The epilogue stages 32-row x 64-column pieces of a wave's
 // accumulators through LDS so that global stores (and residual loads) are 16-byte rows.
 #include "common.hpp"
-
-#include <type_traits>
 
 namespace sd {
 
@@ -269,90 +267,96 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     const float alpha = P.alpha;
     const uint16_t* bias = P.bias;
     constexpr int NOUT = GEGLU ? NI / 2 : NI;   // 32-column output blocks per wave
-    constexpr int WCOLS = NOUT * 32;            // output columns per wave
-    constexpr int LPR = WCOLS / 4;              // lanes per staged row (4 columns each)
+    constexpr int CB = NOUT < 2 ? NOUT : 2;     // 32-column blocks staged per pass (<= 64 columns)
+    constexpr int CCOLS = CB * 32;              // staged columns
+    constexpr int LPR = CCOLS / 4;              // lanes per staged row (4 columns each)
     constexpr int RPP = 64 / LPR;               // rows per pass
+    static_assert(NOUT % CB == 0, "column chunking");
     const int wn_out = GEGLU ? (wn >> 1) : wn;
     const bool y_f32 = P.y_f32 != 0;
     const int lr = lane / LPR, lcol = (lane % LPR) * 4;
-    const int q4 = n0 + wn_out + lcol;
-    // 16-byte path: whole 4-column piece inside N and rows 16-byte aligned
-    const bool vec_ok = (q4 + 4 <= N) && ((P.ldy & 3) == 0) && (!P.res || (P.ldr & 3) == 0);
+    const bool ld_ok = ((P.ldy & 3) == 0) && (!P.res || (P.ldr & 3) == 0);
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        // 1) registers -> staging (value after alpha, bias, GEGLU)
 #pragma unroll
-        for (int nj = 0; nj < NOUT; ++nj) {
-            const int q = n0 + wn_out + nj * 32 + l32;
-            float bv = 0.f, bg = 0.f;
-            if (bias && !P.bias_on_rows && q < N) {
-                bv = bf16_to_f32(bias[q]);
-                if (GEGLU) bg = bf16_to_f32(bias[q + P.geglu_F]);
-            }
+        for (int cc = 0; cc < NOUT / CB; ++cc) {
+            // 1) registers -> staging (value after alpha, bias, GEGLU)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int rr = 8 * (v >> 2) + 4 * hi + (v & 3);
-                float val;
-                if (GEGLU) {
-                    const float a = alpha * acc[mi][2 * nj][v] + bv;
-                    const float gt = alpha * acc[mi][2 * nj + 1][v] + bg;
-                    val = a * gelu_erf(gt);
-                } else {
-                    val = alpha * acc[mi][nj][v] + bv;
+            for (int cj = 0; cj < CB; ++cj) {
+                const int nj = cc * CB + cj;
+                const int q = n0 + wn_out + nj * 32 + l32;
+                float bv = 0.f, bg = 0.f;
+                if (bias && !P.bias_on_rows && q < N) {
+                    bv = bf16_to_f32(bias[q]);
+                    if (GEGLU) bg = bf16_to_f32(bias[q + P.geglu_F]);
                 }
-                stage[rr * EPI_STRIDE + nj * 32 + l32] = val;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int rr = 8 * (v >> 2) + 4 * hi + (v & 3);
+                    float val;
+                    if (GEGLU) {
+                        const float a = alpha * acc[mi][2 * nj][v] + bv;
+                        const float gt = alpha * acc[mi][2 * nj + 1][v] + bg;
+                        val = a * gelu_erf(gt);
+                    } else {
+                        val = alpha * acc[mi][nj][v] + bv;
+                    }
+                    stage[rr * EPI_STRIDE + cj * 32 + l32] = val;
+                }
             }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        // 2) staging -> global: lane handles 4 consecutive columns of one row per pass
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // 2) staging -> global: lane handles 4 consecutive columns of one row per pass
+            const int q4 = n0 + wn_out + cc * CCOLS + lcol;
+            const bool vec_ok = ld_ok && (q4 + 4 <= N);   // 16-byte path: whole piece inside N, aligned rows
 #pragma unroll 2
-        for (int pass = 0; pass < 32 / RPP; ++pass) {
-            const int rr = pass * RPP + lr;
-            const int p = m0 + wm + mi * 32 + rr;
-            if (p < Mp && q4 < N) {
-                f32x4 val = *reinterpret_cast<const f32x4*>(stage + rr * EPI_STRIDE + lcol);
-                if (bias && P.bias_on_rows) val += bf16_to_f32(bias[p]);
-                const int64_t oi = (int64_t)p * P.ldy + q4;
-                const int64_t ri = (int64_t)p * P.ldr + q4;
-                if (y_f32) {
-                    float* yp = static_cast<float*>(P.y) + oi;
-                    const float* rp = static_cast<const float*>(P.res);
-                    if (vec_ok) {
-                        if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
-                        *reinterpret_cast<f32x4*>(yp) = val;
-                    } else {
+            for (int pass = 0; pass < 32 / RPP; ++pass) {
+                const int rr = pass * RPP + lr;
+                const int p = m0 + wm + mi * 32 + rr;
+                if (p < Mp && q4 < N) {
+                    f32x4 val = *reinterpret_cast<const f32x4*>(stage + rr * EPI_STRIDE + lcol);
+                    if (bias && P.bias_on_rows) val += bf16_to_f32(bias[p]);
+                    const int64_t oi = (int64_t)p * P.ldy + q4;
+                    const int64_t ri = (int64_t)p * P.ldr + q4;
+                    if (y_f32) {
+                        float* yp = static_cast<float*>(P.y) + oi;
+                        const float* rp = static_cast<const float*>(P.res);
+                        if (vec_ok) {
+                            if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
+                            *reinterpret_cast<f32x4*>(yp) = val;
+                        } else {
 #pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (q4 + e < N) yp[e] = val[e] + (rp ? rp[ri + e] : 0.f);
-                    }
-                } else {
-                    uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
-                    const uint16_t* rp = static_cast<const uint16_t*>(P.res);
-                    if (vec_ok) {
-                        if (rp) {
-                            const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
-                            val[0] += bf16lo_to_f32(rv[0]); val[1] += bf16hi_to_f32(rv[0]);
-                            val[2] += bf16lo_to_f32(rv[1]); val[3] += bf16hi_to_f32(rv[1]);
+                            for (int e = 0; e < 4; ++e)
+                                if (q4 + e < N) yp[e] = val[e] + (rp ? rp[ri + e] : 0.f);
                         }
-                        bf16x4 o;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
-                        *reinterpret_cast<bf16x4*>(yp) = o;
                     } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (q4 + e < N) {
-                                const float f = val[e] + (rp ? bf16_to_f32(rp[ri + e]) : 0.f);
-                                yp[e] = __builtin_bit_cast(uint16_t, (__bf16)f);
+                        uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
+                        const uint16_t* rp = static_cast<const uint16_t*>(P.res);
+                        if (vec_ok) {
+                            if (rp) {
+                                const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
+                                val[0] += bf16lo_to_f32(rv[0]); val[1] += bf16hi_to_f32(rv[0]);
+                                val[2] += bf16lo_to_f32(rv[1]); val[3] += bf16hi_to_f32(rv[1]);
                             }
+                            bf16x4 o;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
+                            *reinterpret_cast<bf16x4*>(yp) = o;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (q4 + e < N) {
+                                    const float f = val[e] + (rp ? bf16_to_f32(rp[ri + e]) : 0.f);
+                                    yp[e] = __builtin_bit_cast(uint16_t, (__bf16)f);
+                                }
+                        }
                     }
                 }
             }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -381,7 +385,6 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     SD_REQUIRE(g.n >= 1 && g.n <= GEMM_MAX_PROBLEMS, SD_EINVAL, "gemm group: %d problems", g.n);
     bool geglu = g.p[0].geglu_F > 0;
     bool guard = false;
-    long tiles256 = 0;
     int maxN = 0;
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
@@ -393,8 +396,6 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
                    "gemm problem %d: leading dimensions must be multiples of 8", i);
         if (P.Mp == 0 || P.N == 0) continue;
         if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
-        int bo = geglu ? 64 : 128;
-        tiles256 += (long)((P.Mp + 255) / 256) * ((P.N + bo - 1) / bo);
         if (P.N > maxN) maxN = P.N;
     }
     // drop empty problems
@@ -408,7 +409,6 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // workgroups per CU so one workgroup's prologue and epilogue overlap the other's main
     // loop) beat 256x128 tiles at every shape of the transformer block.  Down-projections
     // (N = rank <= 64) use 64x64 tiles with a 5-stage ring.
-    (void)tiles256;
     if (geglu) return launch_cfg<128, 128, 64, 2, 2, 2, true>(g, guard, stream);
     if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false>(g, guard, stream);
     return launch_cfg<128, 128, 64, 2, 2, 2, false>(g, guard, stream);

@@ -15,10 +15,6 @@ namespace sd {
 
 // streaming accesses: W, W' and the undo record are touched exactly once per pass
 typedef float nt_f32x4 __attribute__((ext_vector_type(4)));
-#ifdef EXP_NO_NT
-#define NT_LOAD4(p) (*reinterpret_cast<const float4*>(p))
-#define NT_STORE4(p, v) (*reinterpret_cast<float4*>(p) = (v))
-#else
 __device__ __forceinline__ float4 nt_load4(const float* p) {
     nt_f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const nt_f32x4*>(p));
     return float4{t[0], t[1], t[2], t[3]};
@@ -29,7 +25,6 @@ __device__ __forceinline__ void nt_store4(float* p, float4 v) {
 }
 #define NT_LOAD4(p) nt_load4(p)
 #define NT_STORE4(p, v) nt_store4(p, v)
-#endif
 
 struct PatchPlanEntry {
     sd_patch_desc d;       // 48 bytes
