@@ -36,7 +36,7 @@ static void timing_mark(int tag, int which, hipStream_t stream) {
     if (!g_timing.on || tag < 0) return;
     int& n = g_timing.count[tag];
     if (n >= g_timing.cap) return;
-    hipEventRecord(g_timing.ev[tag][which][n], stream);
+    (void)hipEventRecord(g_timing.ev[tag][which][n], stream);
     if (which == 1) ++n;
 }
 
@@ -256,7 +256,7 @@ extern "C" int sd_timing_disable(void) {
     g_timing.on = false;
     for (int t = 0; t < SD_TIMING_TAGS; ++t)
         for (int w = 0; w < 2; ++w) {
-            for (hipEvent_t e : g_timing.ev[t][w]) hipEventDestroy(e);
+            for (hipEvent_t e : g_timing.ev[t][w]) (void)hipEventDestroy(e);
             g_timing.ev[t][w].clear();
         }
     g_timing.cap = 0;

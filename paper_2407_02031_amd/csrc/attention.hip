@@ -10,8 +10,12 @@
 // the second MFMA, O^T += V^T P^T.  V is consumed transposed ([C, keys]), which is how the
 // v-projection GEMM writes it, so both K and V^T tiles are staged with 16-byte rows.
 //
-// Workgroup: 4 wavefronts, each owning 32*QB queries; K / V^T tiles of 64 keys are staged
-// in LDS (XOR-swizzled 16-byte chunks), double-buffered against the global loads.
+// Workgroup: 4 wavefronts, each owning 32*QB queries; K / V^T tiles of 64 keys go from
+// global memory straight into LDS rings (wave-wide 1 KB loads of XOR-swizzled 16-byte
+// chunks), one tile ahead of the one being used.  K rows are placed in LDS with the keys
+// of every 16-key group in the order [0-3, 8-11, 4-7, 12-15]: the score accumulator of a
+// lane then holds 8 consecutive keys per 16-key group, and the matching V^T operand is a
+// single 16-byte LDS read of the plain [C, keys] layout.
 #include "common.hpp"
 
 namespace sd {
@@ -20,6 +24,25 @@ __device__ __forceinline__ int aswz(int row, int chunk) { return chunk ^ ((row >
 
 constexpr float RESCALE_LOG2 = 8.0f;
 
+// where lanes of a direct-to-LDS load point when their V^T chunk lies past the padded keys
+__device__ __attribute__((aligned(256))) uint32_t g_attn_zeros[64];
+
+// one direct global -> LDS load: each lane fetches 16 bytes from its own address, the 64
+// pieces land contiguously at LDS byte address `lds_base` (wave-uniform).  Completion is
+// tracked by hand with vmcnt and a workgroup barrier.
+__device__ __forceinline__ void attn_dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+// same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane: the
+// per-tile address arithmetic stays on the scalar unit
+__device__ __forceinline__ void attn_dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void attn_wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 template <int QB>
 __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
                                                         const uint16_t* __restrict__ k, int64_t ldk,
@@ -27,8 +50,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
                                                         uint16_t* __restrict__ out, int64_t ldo,
                                                         int Tq, int Tk, int Tkp, int heads, int qtiles, float c) {
     constexpr int BQ = 4 * 32 * QB;
-    __shared__ u32x4 ldsK[2][64 * 8];   // [key][8 chunks of 8 d], 2-deep ring
-    __shared__ u32x4 ldsV[3][64 * 8];   // [d][8 chunks of 8 keys, key order permuted], 3-deep ring
+    __shared__ u32x4 ldsK[2][64 * 8];   // [key (permuted within 16)][8 chunks of 8 d], 2-deep ring
+    __shared__ u32x4 ldsV[3][64 * 8];   // [d][8 chunks of 8 keys], 3-deep ring
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
     // (sample, head, query tile) so that one head's K and V stay in one XCD's L2.
@@ -37,7 +60,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     if ((total & 7) == 0) wi = (wi & 7) * (total >> 3) + (wi >> 3);
     const int qt = wi % qtiles;
     const int head = (wi / qtiles) % heads, b = wi / (qtiles * heads);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int q0 = qt * BQ + wave * 32 * QB;
 
@@ -52,50 +76,64 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         for (int kk = 0; kk < 4; ++kk) qf[qb][kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qp + kk * 16));
     }
 
-    // ---- tile loaders: thread owns chunks (row lrow, lrow + 32; chunk lc) of both tiles
-    const int lrow = tid >> 3, lc = tid & 7;
-    const uint16_t* kbase = k + (int64_t)b * Tk * ldk + head * 64 + lc * 8;
-    const uint16_t* vbase = vt + (int64_t)(head * 64) * ldvt + (int64_t)b * Tkp + lc * 8;
-    u32x4 rk[2], rv[2];
-    auto load_kv = [&](int t) {
+    // ---- tile loaders.  A tile is 8 blocks of 1 KB (8 rows x 8 chunks); load j of wave w
+    // fills block j*4 + w: lane l lands at chunk position l % 8 of row l / 8 and fetches the
+    // logical chunk the XOR swizzle places there.  K row r holds key (r with bits 2 and 3
+    // exchanged); keys past Tk re-read the last key (masked later), V^T chunks past the
+    // padded key count read zeros.
+    const uint32_t ldsK_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ldsK;
+    const uint32_t ldsV_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)ldsV;
+    const uint16_t* kbase = k + (int64_t)b * Tk * ldk + head * 64;
+    // rows of the two loads of a lane are 32 apart: same swizzled chunk for both
+    const int r0 = wave * 8 + (lane >> 3);
+    const int kc8 = aswz(r0, lane & 7) * 8;
+    const int kkey0 = (r0 & ~12) | ((r0 & 4) << 1) | ((r0 & 8) >> 1);
+    // full tiles: byte offsets of this lane's two K rows and two V^T rows from the tile's base
+    uint32_t koff[2], voff[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        koff[j] = (uint32_t)(((int64_t)(kkey0 + j * 32) * ldk + kc8) * 2);
+        voff[j] = (uint32_t)(((int64_t)(r0 + j * 32) * ldvt + kc8) * 2);
+    }
+    const char* vbase = reinterpret_cast<const char*>(vt + (int64_t)(head * 64) * ldvt + (int64_t)b * Tkp);
+    const bool ragged = (Tk & 63) != 0;
+    const int nt = (Tk + 63) >> 6;
+    auto issue_kv = [&](int t, int kslot, int vslot) {
         const int key0 = t * 64;
+        const uint32_t kdst = ldsK_base + (uint32_t)(kslot * 8192 + wave * 1024);
+        const uint32_t vdst = ldsV_base + (uint32_t)(vslot * 8192 + wave * 1024);
+        if (ragged && t == nt - 1) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = lrow + i * 32;
-            int key = key0 + r;
-            key = key < Tk ? key : Tk - 1;
-            rk[i] = *reinterpret_cast<const u32x4*>(kbase + (int64_t)key * ldk);
-            const int kc = key0 + lc * 8;   // first key of this V^T chunk
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (kc < Tkp) {
-                v = *reinterpret_cast<const u32x4*>(vbase + (int64_t)r * ldvt + key0);
-                if (kc + 8 > Tk) {   // zero the padding keys: 0 * garbage must stay 0
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        uint32_t w = v[e];
-                        if (kc + 2 * e >= Tk) w &= 0xffff0000u;
-                        if (kc + 2 * e + 1 >= Tk) w &= 0x0000ffffu;
-                        v[e] = w;
-                    }
-                }
+            for (int j = 0; j < 2; ++j) {
+                int key = key0 + kkey0 + j * 32;
+                key = key < Tk ? key : Tk - 1;
+                attn_dma16(kbase + (int64_t)key * ldk + kc8, kdst + j * 4096);
             }
-            rv[i] = v;
+            const bool inside = key0 + kc8 < Tkp;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const void* src = inside ? (const void*)(vbase + key0 * 2 + voff[j]) : (const void*)g_attn_zeros;
+                attn_dma16(src, vdst + j * 4096);
+            }
+        } else {
+            const char* kb = reinterpret_cast<const char*>(kbase) + (int64_t)key0 * ldk * 2;
+            const char* vb = vbase + key0 * 2;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) attn_dma16_so(kb, koff[j], kdst + j * 4096);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) attn_dma16_so(vb, voff[j], vdst + j * 4096);
         }
     };
-    // K rows go in as they are.  V^T rows are stored with the keys of every 16-key group
-    // permuted to [0-3, 8-11, 4-7, 12-15], the order in which the score accumulator of one
-    // half-wavefront holds them, so the MFMA operand is a single 16-byte read.
-    auto store_kv = [&](int kslot, int vslot) {
-        u32x2* lv2 = reinterpret_cast<u32x2*>(ldsV[vslot]);
+    // padding keys [Tk, Tkp) of the last tile hold whatever the caller's buffer held: zero
+    // them in LDS so that 0 * garbage stays 0 (thread: row tid / 4, keys Tk + tid % 4 (+ 4))
+    auto zero_pad_keys = [&](int t, int vslot) {
+        uint16_t* lv = reinterpret_cast<uint16_t*>(ldsV[vslot]);
+        const int d = tid >> 2;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int r = lrow + i * 32;
-            ldsK[kslot][r * 8 + aswz(r, lc)] = rk[i];
-            const int c0 = aswz(r, lc & ~1);           // physical chunk of the group's first half
-            const int c1 = c0 ^ 1;
-            const u32x2 lo = {rv[i][0], rv[i][1]}, hh = {rv[i][2], rv[i][3]};
-            lv2[(r * 8 + c0) * 2 + (lc & 1)] = lo;
-            lv2[(r * 8 + c1) * 2 + (lc & 1)] = hh;
+            const int key = Tk + (tid & 3) + 4 * i;
+            const int kl = key - t * 64;
+            if (key < Tkp && kl < 64) lv[(d * 8 + aswz(d, kl >> 3)) * 8 + (kl & 7)] = 0;
         }
     };
 
@@ -137,7 +175,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int key = t * 64 + kb * 32 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                const int key = t * 64 + kb * 32 + 16 * (v >> 3) + 8 * hi + (v & 7);
                 if (key >= Tk) {
 #pragma unroll
                     for (int qb = 0; qb < QB; ++qb) s[qb][kb][v] = -INFINITY;
@@ -197,8 +235,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             l[qb] += ls0 + ls1;
         }
     };
-    // O^T += V^T P^T.  k-slot j of sub-step (kb, g2) is key kb*32 + 16*g2 + 8*(j/4) + 4*hi + j%4,
-    // which is the 16-byte piece (2*(kb*2+g2) + hi) of the permuted V^T row
+    // O^T += V^T P^T.  With the K row order above, accumulator register v of block kb is key
+    // kb*32 + 16*(v/8) + 8*hi + v%8: sub-step (kb, g2) multiplies keys kb*32 + 16*g2 + 8*hi ..+8,
+    // the 16-byte chunk kb*4 + g2*2 + hi of a V^T row
     auto accumulate_o = [&](int vslot, bf16x8 (&pf)[QB][2][2]) {
         const u32x4* lv = ldsV[vslot];
 #pragma unroll
@@ -215,13 +254,13 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
                 }
     };
 
-    // ---- prologue: tiles 0 and 1 into LDS, S of tile 0
-    const int nt = (Tk + 63) >> 6;
-    load_kv(0);
-    store_kv(0, 0);
+    // ---- prologue: tiles 0 and 1 in flight, S of tile 0
+    issue_kv(0, 0, 0);
     if (nt > 1) {
-        load_kv(1);
-        store_kv(1, 1);
+        issue_kv(1, 1, 1);
+        attn_wait_vmcnt<4>();
+    } else {
+        attn_wait_vmcnt<0>();
     }
     __syncthreads();
     f32x16 sa[QB][2], sb[QB][2];
@@ -233,20 +272,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     // roles), the last tile is peeled: nothing to prefetch, and only it may need masking.
     int vslot = 0;
     bf16x8 pf[QB][2][2];
-    // one pipelined step: finish tile t (scores in `cur`), start tile t+1 (scores into `nxt`)
+    // One pipelined step: finish tile t (scores in `cur`), start tile t+1 (scores into `nxt`).
+    // On entry tile t+1 is the only load in flight: wait for this wave's part, barrier (all
+    // of tile t+1 is in LDS, every wave is done with step t-1), then refill the slots step
+    // t-1 read last (K slot t%2 held K(t), V slot (t+2)%3 held V(t-1)) with tile t+2.
     auto step = [&](int t, f32x16 (&cur)[QB][2], f32x16 (&nxt)[QB][2]) {
-        const bool pre = t + 2 < nt;
-        if (pre) load_kv(t + 2);
+        attn_wait_vmcnt<0>();
+        __syncthreads();
+        const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
+        if (t + 2 < nt) issue_kv(t + 2, t & 1, vnext2);
         update_max(cur);
         compute_s(t + 1, nxt);
         exponentials(cur, pf);
         accumulate_o(vslot, pf);
-        // tile t+2: K slot t%2 was last read for S(t) one step ago, V slot (t+2)%3 for
-        // tile t-1: both free since the previous barrier
-        const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
-        if (pre) store_kv(t & 1, vnext2);
         vslot = vslot == 2 ? 0 : vslot + 1;
-        __syncthreads();
     };
     int t = 0;
 #pragma unroll 1
@@ -256,16 +295,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     }
     if (t + 1 < nt) {            // one more pipelined step, last tile's scores end up in sb
         step(t, sa, sb);
-        if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sb);
+        if (ragged) mask_tail(nt - 1, sb);
         update_max(sb);
         exponentials(sb, pf);
-        accumulate_o(vslot, pf);
     } else {                     // last tile's scores are in sa
-        if ((nt - 1) * 64 + 64 > Tk) mask_tail(nt - 1, sa);
+        if (ragged) mask_tail(nt - 1, sa);
         update_max(sa);
         exponentials(sa, pf);
-        accumulate_o(vslot, pf);
     }
+    // the last tile's V^T landed before the barrier of the step before (or of the prologue)
+    if (Tk & 7) {
+        zero_pad_keys(nt - 1, vslot);
+        __syncthreads();
+    }
+    accumulate_o(vslot, pf);
 
     // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
 #pragma unroll
@@ -294,6 +337,7 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
     SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
     SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
+    SD_REQUIRE(ldk > 0 && ldvt > 0 && ldk < (1 << 23) && ldvt < (1 << 23), SD_EINVAL, "attention: leading dimensions out of range");
     if (Bn <= 0 || Tq <= 0 || heads <= 0) return SD_OK;
     const float c = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
     const int qtiles = (Tq + 127) / 128;

@@ -55,6 +55,11 @@ __device__ __attribute__((aligned(256))) uint32_t g_gemm_zeros[64];
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
 }
+// Same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane, which
+// keeps the per-step address arithmetic on the scalar unit.
+__device__ __forceinline__ void dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -140,46 +145,62 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
 
     // ---- loader.  Load j of wave w fills 1 KB block (j*NW + w) of a stage: RPB tile rows
     // (P rows first, then Q rows) of CPR chunks; lane l lands at chunk position l % CPR of row
-    // l / CPR, so it must fetch the logical chunk that the XOR swizzle places there.
-    const uint16_t* gp0[LPT];    // this lane's source (row start + chunk) per load, K segment 0
-    const uint16_t* gp1[LPT];    // ... K segment 1 (LoRA); equals gp0 when there is none
-    int kcol[LPT];               // first k of that chunk within a tile
+    // l / CPR, so it must fetch the logical chunk that the XOR swizzle places there.  The
+    // first JP loads of a lane are P rows, the rest Q rows; a lane's source is a wave-uniform
+    // base (operand start + k offset of the step, scalar arithmetic) plus a constant 32-bit
+    // byte offset (row, chunk).
+    constexpr int JP = (BM / RPB) / NW;
+    static_assert((BM / RPB) % NW == 0, "P/Q split must fall on a load index");
+    uint32_t off0[LPT];          // byte offset of this lane's chunk from the operand start, K segment 0
+    uint32_t off1[LPT];          // ... K segment 1 (LoRA); equals off0 when there is none
+    int kcol[GUARD ? LPT : 1];   // first k of that chunk within a tile (only partial tiles need it)
+    const uint16_t* const pb0 = P.p0 + (int64_t)m0 * P.ldp0;
+    const uint16_t* const pb1 = K1 ? P.p1 + (int64_t)m0 * P.ldp1 : pb0;
+    const uint16_t* const qb0 = P.q0 + (int64_t)n0 * P.ldq0;
+    const uint16_t* const qb1 = K1 ? P.q1 + (int64_t)n0 * P.ldq1 : qb0;
     {
-        const uint16_t* p0 = P.p0; const uint16_t* q0 = P.q0;
-        const uint16_t* p1 = K1 ? P.p1 : P.p0; const uint16_t* q1 = K1 ? P.q1 : P.q0;
         const int64_t ldp0 = P.ldp0, ldq0 = P.ldq0;
         const int64_t ldp1 = K1 ? P.ldp1 : P.ldp0, ldq1 = K1 ? P.ldq1 : P.ldq0;
 #pragma unroll
         for (int j = 0; j < LPT; ++j) {
             const int row = (j * NW + wave) * RPB + lane / CPR;    // row within the stage
             const int c = swz<CPR>(row, lane % CPR);               // logical chunk fetched by this lane
-            kcol[j] = c * 8;
-            if (row < BM) {
+            if (GUARD) kcol[j] = c * 8;
+            if (j < JP) {
                 int r = m0 + row;
-                r = r < Mp ? r : Mp - 1;
-                gp0[j] = p0 + (int64_t)r * ldp0 + c * 8;
-                gp1[j] = p1 + (int64_t)r * ldp1 + c * 8;
+                r = (r < Mp ? r : Mp - 1) - m0;
+                off0[j] = (uint32_t)((r * ldp0 + c * 8) * 2);
+                off1[j] = (uint32_t)((r * ldp1 + c * 8) * 2);
             } else {
-                const int qr = qrow(row - BM);
-                gp0[j] = q0 + (int64_t)qr * ldq0 + c * 8;
-                gp1[j] = q1 + (int64_t)qr * ldq1 + c * 8;
+                const int qr = qrow(row - BM) - n0;
+                off0[j] = (uint32_t)((qr * ldq0 + c * 8) * 2);
+                off1[j] = (uint32_t)((qr * ldq1 + c * 8) * 2);
             }
         }
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
     const uint32_t wave_base = lds_base + (uint32_t)wave * 1024;
-    // issue the loads of k-step t into ring stage `stg` (branch-free: both segments' pointers
-    // are precomputed, the step picks one)
+    // issue the loads of k-step t into ring stage `stg`.  A partial last tile of a segment
+    // (GUARD only) takes per-lane 64-bit addresses so that chunks past the segment's end can
+    // point at the zero page.
     auto issue_tile = [&](int t, int stg) {
         const bool s1 = t >= nk0;
         const int kb = (s1 ? t - nk0 : t) * BK;
         const int Kseg = s1 ? K1 : K0;
         const uint32_t sbase = wave_base + (uint32_t)stg * (STAGE * 16);
+        const uint16_t* pb = (s1 ? pb1 : pb0) + kb;
+        const uint16_t* qb = (s1 ? qb1 : qb0) + kb;
+        if (GUARD && kb + BK > Kseg) {
 #pragma unroll
-        for (int j = 0; j < LPT; ++j) {
-            const void* src = (s1 ? gp1[j] : gp0[j]) + kb;
-            if (GUARD) src = (kb + kcol[j] < Kseg) ? src : (const void*)g_gemm_zeros;
-            dma16(src, sbase + (uint32_t)j * (NW * 1024));
+            for (int j = 0; j < LPT; ++j) {
+                const char* src = reinterpret_cast<const char*>(j < JP ? pb : qb) + (s1 ? off1[j] : off0[j]);
+                src = (kb + kcol[GUARD ? j : 0] < Kseg) ? src : reinterpret_cast<const char*>(g_gemm_zeros);
+                dma16(src, sbase + (uint32_t)j * (NW * 1024));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < LPT; ++j)
+                dma16_so(j < JP ? pb : qb, s1 ? off1[j] : off0[j], sbase + (uint32_t)j * (NW * 1024));
         }
     };
 
@@ -394,6 +415,11 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         SD_REQUIRE(P.p0 && P.q0 && P.y && (P.K1 == 0 || (P.p1 && P.q1)), SD_EINVAL, "gemm problem %d: null operand", i);
         SD_REQUIRE(P.ldp0 % 8 == 0 && P.ldq0 % 8 == 0 && (P.K1 == 0 || (P.ldp1 % 8 == 0 && P.ldq1 % 8 == 0)), SD_EINVAL,
                    "gemm problem %d: leading dimensions must be multiples of 8", i);
+        // lane offsets inside a tile are 32-bit byte offsets
+        const int64_t span = 256 + (P.geglu_F > 0 ? P.geglu_F : 0);
+        SD_REQUIRE(P.ldp0 > 0 && P.ldq0 > 0 && P.ldp0 * 256 < (1ll << 31) && P.ldq0 * span < (1ll << 31) &&
+                       (P.K1 == 0 || (P.ldp1 > 0 && P.ldq1 > 0 && P.ldp1 * 256 < (1ll << 31) && P.ldq1 * span < (1ll << 31))),
+                   SD_EINVAL, "gemm problem %d: leading dimension out of range", i);
         if (P.Mp == 0 || P.N == 0) continue;
         if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
         if (P.N > maxN) maxN = P.N;
