@@ -36,7 +36,7 @@ __device__ __forceinline__ void attn_dma16(const void* gptr, uint32_t lds_base) 
 // same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane: the
 // per-tile address arithmetic stays on the scalar unit
 __device__ __forceinline__ void attn_dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void attn_wait_vmcnt() {
@@ -149,9 +149,22 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             for (int v = 0; v < 16; ++v) o[qb][db][v] = 0.f;
     }
 
-    // S^T tile of key tile t: 64 keys x (32*QB) queries
-    auto compute_s = [&](int t, f32x16 (&s)[QB][2]) {
+    // S^T tile of key tile t: 64 keys x (32*QB) queries.  The K fragments of the first two
+    // k-steps are fetched by the caller ahead of time (their LDS latency hides behind the
+    // running-maximum update), the other two are read here.
+    auto load_kfrags = [&](int t, int kk0, bf16x8 (&kf)[2][2]) {
         const u32x4* lk = ldsK[t & 1];
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const int r = kb * 32 + l32;
+                kf[kk][kb] = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, (kk0 + kk) * 2 + hi)]);
+            }
+    };
+    auto compute_s = [&](int t, f32x16 (&s)[QB][2], bf16x8 (&kf0)[2][2]) {
+        bf16x8 kf1[2][2];
+        load_kfrags(t, 2, kf1);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
@@ -162,8 +175,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const int r = kb * 32 + l32;
-                const bf16x8 a = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, kk * 2 + hi)]);
+                const bf16x8 a = kk < 2 ? kf0[kk][kb] : kf1[kk - 2][kb];
 #pragma unroll
                 for (int qb = 0; qb < QB; ++qb)
                     s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[qb][kk], s[qb][kb], 0, 0, 0);
@@ -192,7 +204,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             float mx = fmaxf(s[qb][0][0], s[qb][1][0]);
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[qb][0][v]), s[qb][1][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            // the other half-wavefront holds the other 32 keys of this query: exchange the
+            // two halves with a lane swap (a vector-ALU operation, no LDS round trip)
+            const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, mx), __builtin_bit_cast(uint32_t, mx), false, false);
+            mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
             const bool need = (mx - m[qb]) * c > RESCALE_LOG2;
             if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
                 const float mnew = need ? mx : m[qb];
@@ -264,7 +279,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     }
     __syncthreads();
     f32x16 sa[QB][2], sb[QB][2];
-    compute_s(0, sa);
+    {
+        bf16x8 kf0[2][2];
+        load_kfrags(0, 0, kf0);
+        compute_s(0, sa, kf0);
+    }
 
     // ---- main loop, software-pipelined: the score MFMAs of tile t+1 are independent of the
     // exponentials of tile t and sit in the same basic block, so the matrix pipe and the
@@ -281,8 +300,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         __syncthreads();
         const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
         if (t + 2 < nt) issue_kv(t + 2, t & 1, vnext2);
+        bf16x8 kf0[2][2];
+        load_kfrags(t + 1, 0, kf0);
+        __builtin_amdgcn_sched_barrier(0);
         update_max(cur);
-        compute_s(t + 1, nxt);
+        compute_s(t + 1, nxt, kf0);
         exponentials(cur, pf);
         accumulate_o(vslot, pf);
         vslot = vslot == 2 ? 0 : vslot + 1;

@@ -58,7 +58,7 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
 // Same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane, which
 // keeps the per-step address arithmetic on the scalar unit.
 __device__ __forceinline__ void dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(sbase) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
