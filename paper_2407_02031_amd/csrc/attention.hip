@@ -31,12 +31,12 @@ __device__ __attribute__((aligned(256))) uint32_t g_attn_zeros[64];
 // pieces land contiguously at LDS byte address `lds_base` (wave-uniform).  Completion is
 // tracked by hand with vmcnt and a workgroup barrier.
 __device__ __forceinline__ void attn_dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr) : "memory", "m0");
 }
 // same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane: the
 // per-tile address arithmetic stays on the scalar unit
 __device__ __forceinline__ void attn_dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void attn_wait_vmcnt() {
@@ -206,8 +206,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             for (int v = 1; v < 16; ++v) mx = fmaxf(fmaxf(mx, s[qb][0][v]), s[qb][1][v]);
             // the other half-wavefront holds the other 32 keys of this query: exchange the
             // two halves with a lane swap (a vector-ALU operation, no LDS round trip)
-            const auto sw = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(uint32_t, mx), __builtin_bit_cast(uint32_t, mx), false, false);
-            mx = fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+            float mx_lo, mx_hi;
+            both_halves(mx, mx_lo, mx_hi);
+            mx = fmaxf(mx_lo, mx_hi);
             const bool need = (mx - m[qb]) * c > RESCALE_LOG2;
             if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
                 const float mnew = need ? mx : m[qb];
@@ -335,7 +336,9 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        const float lt = l[qb] + __shfl_xor(l[qb], 32, 64);
+        float l_lo, l_hi;
+        both_halves(l[qb], l_lo, l_hi);   // the two half-wavefronts summed different keys of the same query
+        const float lt = l_lo + l_hi;
         const float inv = 1.0f / lt;
         const int row = q0 + qb * 32 + l32;
         if (row < Tq) {

@@ -28,6 +28,15 @@ __device__ __forceinline__ const void* uniform_ptr(const void* p) {
     const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(a >> 32));
     return reinterpret_cast<const void*>((static_cast<uint64_t>(hi) << 32) | lo);
 }
+// Both halves of a wavefront see both halves' values of x: on return lo holds the value of
+// lane (l % 32) and hi that of lane (l % 32) + 32, in every lane.  Written as inline assembly
+// with both registers as read-write operands: given the same value twice, the compiler's
+// builtin for this instruction was seen to fold the two results into one.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
+    lo = x;
+    hi = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }

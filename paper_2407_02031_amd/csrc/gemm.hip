@@ -53,12 +53,12 @@ __device__ __attribute__((aligned(256))) uint32_t g_gemm_zeros[64];
 // tile being multiplied behind loads that target another ring stage; completion is tracked
 // by hand with vmcnt (loads retire in order) and a workgroup barrier.
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr) : "memory", "m0");
 }
 // Same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane, which
 // keeps the per-step address arithmetic on the scalar unit.
 __device__ __forceinline__ void dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {

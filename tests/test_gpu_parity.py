@@ -138,6 +138,28 @@ def test_attention_matches_oracle(B, Bn, Tq, Tk, heads, qscale):
         assert rel_err(O.attention(q, k, np.roll(v, 1, axis=1), heads), ref) > 10 * BF16_TOL
 
 
+def test_attention_large_scores_in_alternate_key_octets(B):
+    """Keys whose index has bit 3 set score ~+770, the others ~-770: a running maximum taken
+    over only part of a tile's keys would overflow the exponentials (the kernel holds the two
+    octets of every 16 keys in different half-wavefronts and must exchange their maxima)."""
+    Bn, Tq, Tk, heads = 1, 96, 160, 1
+    r = rng(77)
+    q = G.bf16_round((1.0 + 0.0625 * r.integers(-2, 3, size=(Bn, Tq, 64))).astype(np.float32))
+    sign = np.where((np.arange(Tk) & 8) != 0, 1.0, -1.0).astype(np.float32)
+    k = G.bf16_round((12.0 * sign)[None, :, None] * np.ones((Bn, Tk, 64), np.float32))
+    v = G.bf16_round(r.standard_normal((Bn, Tk, 64)).astype(np.float32))
+    ref = O.attention(q, k, v, heads)
+    got = host(B.attention_fwd(dev(q, B), dev(k, B), vt_layout(v, B), heads))
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) <= BF16_TOL
+    # and the mirrored pattern
+    k2 = -k
+    ref2 = O.attention(q, k2, v, heads)
+    got2 = host(B.attention_fwd(dev(q, B), dev(k2, B), vt_layout(v, B), heads))
+    assert np.isfinite(got2).all()
+    assert rel_err(got2, ref2) <= BF16_TOL
+
+
 # ------------------------------------------------------- attn_block_fwd / ff_block_fwd
 def small_cfg(**kw):
     base = dict(name="t", Bn=2, T=200, C=128, heads=2, depth=1, r=8, alpha=4.0, lora_ff=True, Tc=77, Dc=256,
