@@ -80,7 +80,7 @@ constexpr int gemm_min_waves() {
     return gemm_lds_chunks<BM, BN, BK, WGM, WGN, STAGES>() * 16 <= 80 * 1024 ? 2 : 1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD>
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD, bool RES32>
 __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WGN, STAGES>())) void gemm_kernel(const GemmGroup g) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
@@ -269,34 +269,61 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
         st = st + 1 == STAGES ? 0 : st + 1;
     }
 #pragma unroll 1
-    for (; t < nkt; ++t) {
+    for (; t + 1 < nkt; ++t) {
         const int newer = nkt - 1 - t;  // tiles issued after tile t
         if (DIST >= 4 && newer >= 3) wait_vmcnt<3 * LPT>();
         else if (DIST >= 3 && newer >= 2) wait_vmcnt<2 * LPT>();
-        else if (DIST >= 2 && newer >= 1) wait_vmcnt<LPT>();
-        else wait_vmcnt<0>();
+        else wait_vmcnt<LPT>();
         __syncthreads();
         compute(st);
         st = st + 1 == STAGES ? 0 : st + 1;
     }
-    __syncthreads();   // ring reads done before the epilogue reuses LDS
+    wait_vmcnt<0>();
+    __syncthreads();
 
-    // ---- epilogue.  Accumulator layout of the 32x32 MFMA: lane holds column l32 and rows
-    // 8*(v/4) + 4*hi + (v%4), v = 0..15.  Each wave stages one 32-row block at a time in its
-    // own LDS region (fp32, padded rows) and writes it out as 16-byte row pieces.
-    float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
-    const float alpha = P.alpha;
-    const uint16_t* bias = P.bias;
+    // ---- epilogue geometry.  Accumulator layout of the 32x32 MFMA: lane holds column l32 and
+    // rows 8*(v/4) + 4*hi + (v%4), v = 0..15.  Each wave stages a 32-row x CCOLS-column piece at
+    // a time in its own LDS region (fp32, padded rows) and writes it out as 16-byte row pieces:
+    // lane handles 4 consecutive columns (lcol) of row lr, lr + RPP, ... of the piece.
     constexpr int NOUT = GEGLU ? NI / 2 : NI;   // 32-column output blocks per wave
     constexpr int CB = NOUT < 2 ? NOUT : 2;     // 32-column blocks staged per pass (<= 64 columns)
     constexpr int CCOLS = CB * 32;              // staged columns
     constexpr int LPR = CCOLS / 4;              // lanes per staged row (4 columns each)
     constexpr int RPP = 64 / LPR;               // rows per pass
+    constexpr int NPASS = 32 / RPP;
     static_assert(NOUT % CB == 0, "column chunking");
     const int wn_out = GEGLU ? (wn >> 1) : wn;
     const bool y_f32 = P.y_f32 != 0;
     const int lr = lane / LPR, lcol = (lane % LPR) * 4;
     const bool ld_ok = ((P.ldy & 3) == 0) && (!P.res || (P.ldr & 3) == 0);
+
+    // fp32 residual: fetch this lane's pieces of the whole wave tile now, so that the loads
+    // fly during the last tile's MFMAs and the epilogue never waits piece by piece
+    f32x4 rpre[RES32 ? MI : 1][RES32 ? NOUT / CB : 1][RES32 ? NPASS : 1];
+    const bool res_pre = RES32 && P.res && y_f32 && ld_ok;
+    if (RES32 && res_pre) {
+        const float* rp = static_cast<const float*>(P.res);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int cc = 0; cc < NOUT / CB; ++cc) {
+                const int q4 = n0 + wn_out + cc * CCOLS + lcol;
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int p = m0 + wm + mi * 32 + pass * RPP + lr;
+                    f32x4 r = {0.f, 0.f, 0.f, 0.f};
+                    if (p < Mp && q4 + 4 <= N) r = *reinterpret_cast<const f32x4*>(rp + (int64_t)p * P.ldr + q4);
+                    rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0] = r;
+                }
+            }
+    }
+    compute(st);
+    __syncthreads();   // ring reads done before the epilogue reuses LDS
+
+    // ---- epilogue
+    float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
+    const float alpha = P.alpha;
+    const uint16_t* bias = P.bias;
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -331,8 +358,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
             // 2) staging -> global: lane handles 4 consecutive columns of one row per pass
             const int q4 = n0 + wn_out + cc * CCOLS + lcol;
             const bool vec_ok = ld_ok && (q4 + 4 <= N);   // 16-byte path: whole piece inside N, aligned rows
-#pragma unroll 2
-            for (int pass = 0; pass < 32 / RPP; ++pass) {
+#pragma unroll
+            for (int pass = 0; pass < NPASS; ++pass) {
                 const int rr = pass * RPP + lr;
                 const int p = m0 + wm + mi * 32 + rr;
                 if (p < Mp && q4 < N) {
@@ -344,7 +371,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
                         float* yp = static_cast<float*>(P.y) + oi;
                         const float* rp = static_cast<const float*>(P.res);
                         if (vec_ok) {
-                            if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
+                            if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
+                            else if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
                             *reinterpret_cast<f32x4*>(yp) = val;
                         } else {
 #pragma unroll
@@ -381,7 +409,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU>
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool RES32>
 static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
     int total = 0;
@@ -395,9 +423,9 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     g.total_tiles = total;
     if (total == 0) return SD_OK;
     if (guard)
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, true>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, true, RES32>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
     else
-        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, false>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
+        hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, STAGES, GEGLU, false, RES32>), dim3(total), dim3(64 * WGM * WGN), 0, stream, g);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
@@ -407,8 +435,10 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     bool geglu = g.p[0].geglu_F > 0;
     bool guard = false;
     int maxN = 0;
+    bool res32 = false;   // some problem adds an fp32 residual: take the kernel that prefetches it
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
+        if (P.res && P.y_f32 && P.Mp > 0 && P.N > 0) res32 = true;
         SD_REQUIRE((P.geglu_F > 0) == geglu, SD_EINVAL, "gemm group mixes GEGLU and plain problems");
         SD_REQUIRE(P.Mp >= 0 && P.N >= 0 && P.K0 > 0 && P.K0 % 8 == 0 && P.K1 >= 0 && P.K1 % 8 == 0, SD_EINVAL,
                    "gemm problem %d: bad sizes M=%d N=%d K0=%d K1=%d", i, P.Mp, P.N, P.K0, P.K1);
@@ -435,9 +465,10 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // workgroups per CU so one workgroup's prologue and epilogue overlap the other's main
     // loop) beat 256x128 tiles at every shape of the transformer block.  Down-projections
     // (N = rank <= 64) use 64x64 tiles with a 5-stage ring.
-    if (geglu) return launch_cfg<128, 128, 64, 2, 2, 2, true>(g, guard, stream);
-    if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false>(g, guard, stream);
-    return launch_cfg<128, 128, 64, 2, 2, 2, false>(g, guard, stream);
+    if (geglu) return launch_cfg<128, 128, 64, 2, 2, 2, true, false>(g, guard, stream);
+    if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false, false>(g, guard, stream);
+    if (res32) return launch_cfg<128, 128, 64, 2, 2, 2, false, true>(g, guard, stream);
+    return launch_cfg<128, 128, 64, 2, 2, 2, false, false>(g, guard, stream);
 }
 
 }  // namespace sd
