@@ -286,7 +286,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     // a time in its own LDS region (fp32, padded rows) and writes it out as 16-byte row pieces:
     // lane handles 4 consecutive columns (lcol) of row lr, lr + RPP, ... of the piece.
     constexpr int NOUT = GEGLU ? NI / 2 : NI;   // 32-column output blocks per wave
-    constexpr int CB = NOUT < 2 ? NOUT : 2;     // 32-column blocks staged per pass (<= 64 columns)
+    constexpr int CB = (NOUT % 2 == 0) ? 2 : 1; // 32-column blocks staged per pass (<= 64 columns)
     constexpr int CCOLS = CB * 32;              // staged columns
     constexpr int LPR = CCOLS / 4;              // lanes per staged row (4 columns each)
     constexpr int RPP = 64 / LPR;               // rows per pass

@@ -60,7 +60,7 @@ def test_patch_plan_build_validates_on_host(B):
     host = np.zeros(128, np.uint8)
     tiles = C.c_int64(-1)
     assert L.sd_patch_plan_build(descs, 2, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)) == 0
-    assert tiles.value == 10 * 1 + 4 * 1     # workgroup tiles of 32 rows x 512 columns
+    assert tiles.value == 10 * 1 + 4 * 1     # workgroup tiles of 32 rows x 256 columns
     plan = host.view(np.int64).reshape(2, 8)
     assert plan[0, 6] == 0 and plan[1, 6] == 10
     # buffer too small
