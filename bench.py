@@ -235,6 +235,31 @@ def main() -> int:
         del mats, plan
         torch.cuda.empty_cache()
 
+    # ---------------------------------------------------------------- measured ceilings
+    # what this device sustains: a register-resident bf16 MFMA loop and a streaming fp32
+    # copy, to set beside the vendor peaks the fractions above are quoted against
+    cout = torch.empty(1024 * 256, dtype=torch.float32, device="cuda")
+    cfl = [0.0]
+
+    def mfma_loop():
+        cfl[0] = B.ceiling_mfma_bf16(cout, 1024, 4000)
+
+    mfma_loop()
+    cm = float(np.median(time_events(mfma_loop, 5)))
+    csrc = torch.randn(1 << 28, device="cuda")           # 1 GiB, well past the last-level cache
+    cdst = torch.empty_like(csrc)
+    B.ceiling_copy_f32(csrc, cdst)
+    cc = float(np.median(time_events(lambda: B.ceiling_copy_f32(csrc, cdst), 5)))
+    mfma_ceiling = cfl[0] / (cm * 1e-3) / 1e12
+    copy_ceiling = 8.0 * csrc.numel() / (cc * 1e-3) / 1e9
+    out["ceilings"] = {"mfma_bf16_tflops": round(mfma_ceiling, 1), "copy_f32_gbs": round(copy_ceiling, 1),
+                       "value_frac_of_mfma_ceiling": round(tflops / mfma_ceiling, 4),
+                       "dominant_kernel_frac_of_mfma_ceiling": round(kernels[dom]["tflops"] / mfma_ceiling, 4)}
+    if "patch" in out:
+        out["ceilings"]["patch_frac_of_copy_ceiling"] = round(out["patch"]["patch_gbs"] / copy_ceiling, 4)
+        out["ceilings"]["unpatch_frac_of_copy_ceiling"] = round(out["patch"]["unpatch_gbs"] / copy_ceiling, 4)
+    del csrc, cdst, cout
+
     # --------------------------------------------------------------------- CPU baseline
     if not args.no_cpu_baseline:
         from oracle import sdxl_block_oracle as O

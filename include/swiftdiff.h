@@ -97,6 +97,17 @@ int sd_timing_enable(int32_t records_per_tag);
 int sd_timing_collect(int32_t tag, float* ms_host, int32_t capacity, int32_t* count);
 int sd_timing_disable(void);
 
+/* ---- measured ceilings (measurement support, not part of the method) --------------------
+ * What this device sustains, to set beside the vendor peaks in a roofline figure.
+ * ceiling_mfma_bf16: `workgroups` x 4 wavefronts each run `iters` x 4 independent
+ *   32x32x16 bf16 MFMAs out of registers; out: device, workgroups * 256 floats (written so
+ *   the loop is not optimised away); *flops (host, may be NULL) receives the FLOP count of
+ *   the launch.  Time it with events on `stream`.
+ * ceiling_copy_f32: dst[i] = src[i] for n floats (n % 4 == 0, 16-byte aligned device
+ *   pointers, no overlap): 8 bytes of traffic per element. */
+int sd_ceiling_mfma_bf16(float* out, int32_t workgroups, int32_t iters, double* flops, void* stream);
+int sd_ceiling_copy_f32(const float* src, float* dst, size_t n, void* stream);
+
 /* ---- lora_linear_fwd ------------------------------------------------------------------
  * y = epi( LN?(x) W^T + bias + scale * (LN?(x) A^T) B^T ) + residual
  * The unmerged form of Section 2's W' = W + A B applied to an input; the rank-r update

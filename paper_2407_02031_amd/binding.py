@@ -66,6 +66,8 @@ def _load() -> C.CDLL:
         "sd_timing_enable": (C.c_int, [i32]),
         "sd_timing_collect": (C.c_int, [i32, P(f32), i32, P(i32)]),
         "sd_timing_disable": (C.c_int, []),
+        "sd_ceiling_mfma_bf16": (C.c_int, [vp, i32, i32, P(C.c_double), vp]),
+        "sd_ceiling_copy_f32": (C.c_int, [vp, vp, sz, vp]),
         "sd_lora_linear_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "sd_lora_linear_fwd": (C.c_int, [vp, i32, P(sd_proj), vp, vp, f32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]),
         "sd_attn_block_workspace_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
@@ -94,7 +96,8 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
+EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32",
+           "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
@@ -315,6 +318,17 @@ def timing_collect(tag: str, capacity: int = 65536) -> List[float]:
 
 def timing_disable() -> None:
     _check(_lib.sd_timing_disable())
+
+
+def ceiling_mfma_bf16(out: torch.Tensor, workgroups: int, iters: int) -> float:
+    """Enqueue the register-resident MFMA loop; returns the FLOPs of the launch."""
+    fl = C.c_double(0.0)
+    _check(_lib.sd_ceiling_mfma_bf16(_ptr(out), workgroups, iters, C.byref(fl), _stream()))
+    return fl.value
+
+
+def ceiling_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
+    _check(_lib.sd_ceiling_copy_f32(_ptr(src), _ptr(dst), src.numel(), _stream()))
 
 
 def lora_patch(plan: PatchPlan) -> None:

@@ -1,0 +1,66 @@
+// Two measured ceilings for the roofline figures, run on the same device as the kernels they
+// are compared with: a register-resident bf16 MFMA loop (no memory traffic at all) and a
+// streaming fp32 copy (one read and one write per element).  Vendor peaks assume the boost
+// clock and ideal DRAM efficiency; these two say what this part sustains.
+#include "common.hpp"
+
+namespace sd {
+
+// 4 independent 32x32x16 accumulators per wavefront, operands with pseudo-random bit patterns
+// (all-equal operands toggle fewer wires and clock higher than real data does)
+__global__ __launch_bounds__(256) void ceiling_mfma_kernel(float* __restrict__ out, int iters) {
+    bf16x8 a, b;
+    uint32_t s = 0x9e3779b9u * (threadIdx.x + 1u) + blockIdx.x;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        s = s * 1664525u + 1013904223u;
+        a[i] = (__bf16)(((int)(s >> 20) - 2048) * (1.0f / 4096.0f));
+        s = s * 1664525u + 1013904223u;
+        b[i] = (__bf16)(((int)(s >> 20) - 2048) * (1.0f / 4096.0f));
+    }
+    f32x16 c[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) c[j][v] = 0.f;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[j], 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) r += c[j][0] + c[j][15];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+
+__global__ __launch_bounds__(256) void ceiling_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, size_t n4) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n4; i += stride) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+}
+
+}  // namespace sd
+
+using namespace sd;
+
+extern "C" int sd_ceiling_mfma_bf16(float* out, int32_t workgroups, int32_t iters, double* flops, void* stream) {
+    SD_REQUIRE(out && workgroups > 0 && iters > 0, SD_EINVAL, "ceiling_mfma: out=%p workgroups=%d iters=%d", (void*)out, workgroups, iters);
+    hipLaunchKernelGGL(ceiling_mfma_kernel, dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
+    SD_HIP_CHECK(hipGetLastError());
+    if (flops) *flops = (double)workgroups * 4.0 /*waves*/ * iters * 4.0 /*MFMAs*/ * (2.0 * 32 * 32 * 16);
+    return SD_OK;
+}
+
+extern "C" int sd_ceiling_copy_f32(const float* src, float* dst, size_t n, void* stream) {
+    SD_REQUIRE(src && dst && aligned16(src) && aligned16(dst), SD_EINVAL, "ceiling_copy: pointers must be non-null and 16-byte aligned");
+    SD_REQUIRE(n % 4 == 0, SD_EINVAL, "ceiling_copy: n must be a multiple of 4");
+    if (n == 0) return SD_OK;
+    const size_t n4 = n / 4;
+    size_t wgs = (n4 + 255) / 256;
+    if (wgs > 65536) wgs = 65536;
+    hipLaunchKernelGGL(ceiling_copy_kernel, dim3((unsigned)wgs), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       reinterpret_cast<const f32x4*>(src), reinterpret_cast<f32x4*>(dst), n4);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
