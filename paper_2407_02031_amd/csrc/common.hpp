@@ -37,6 +37,31 @@ __device__ __forceinline__ void both_halves(float x, float& lo, float& hi) {
     hi = x;
     asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
 }
+// Sum over the 64 lanes of a wavefront, result in every lane, without LDS traffic: four
+// DPP steps inside each row of 16 lanes (swap lane pairs, swap pairs, mirror the half rows,
+// mirror the row: after each step the lanes that were combined hold equal values, so the
+// mirrors act as exchanges), then the row-pair and half-wavefront swaps.
+__device__ __forceinline__ float dpp_add(float v, const int which) {
+    const int x = __builtin_bit_cast(int, v);
+    int y;
+    if (which == 0) y = __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, false);        // quad_perm [1,0,3,2]
+    else if (which == 1) y = __builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, false);   // quad_perm [2,3,0,1]
+    else if (which == 2) y = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xf, 0xf, false);  // row_half_mirror
+    else y = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xf, 0xf, false);                  // row_mirror
+    return v + __builtin_bit_cast(float, y);
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_add(v, 0);
+    v = dpp_add(v, 1);
+    v = dpp_add(v, 2);
+    v = dpp_add(v, 3);
+    float a = v, b = v;   // odd rows of a <-> even rows of b: a + b is the sum of each row pair
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+    v = a + b;
+    float lo, hi;
+    both_halves(v, lo, hi);
+    return lo + hi;
+}
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }

@@ -19,7 +19,6 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const void* __restrict__
     if (row >= M) return;
     const int nch = C >> 2;   // 4-element chunks per row
     float v[LN_MAXJ][4];
-    float s = 0.f;
 #pragma unroll
     for (int j = 0; j < LN_MAXJ; ++j) {
         const int ch = lane + j * 64;
@@ -32,26 +31,37 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const void* __restrict__
                 v[j][0] = bf16lo_to_f32(t.x); v[j][1] = bf16hi_to_f32(t.x);
                 v[j][2] = bf16lo_to_f32(t.y); v[j][3] = bf16hi_to_f32(t.y);
             }
-            s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
         } else {
             v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.f;
         }
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-    const float mean = s / (float)C;
-    float s2 = 0.f;
+    // One pass over the registers for both moments, taken about the row's first element (a
+    // sample of the row, so the variance below loses no digits to a large common offset),
+    // and one reduction for the pair.
+    const float shift = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v[0][0])));
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int j = 0; j < LN_MAXJ; ++j) {
         const int ch = lane + j * 64;
         if (ch < nch) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { v[j][e] -= mean; s2 += v[j][e] * v[j][e]; }
+            for (int e = 0; e < 4; ++e) {
+                v[j][e] -= shift;
+                s1 += v[j][e];
+                s2 += v[j][e] * v[j][e];
+            }
         }
     }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    const float inv_c = 1.0f / (float)C;
+    const float dmean = s1 * inv_c;                      // mean - shift
+    const float var = fmaxf(s2 * inv_c - dmean * dmean, 0.f);
+    const float rstd = rsqrtf(var + eps);
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) s2 += __shfl_xor(s2, o, 64);
-    const float rstd = rsqrtf(s2 / (float)C + eps);
+    for (int j = 0; j < LN_MAXJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[j][e] -= dmean;
 #pragma unroll
     for (int j = 0; j < LN_MAXJ; ++j) {
         const int ch = lane + j * 64;
@@ -127,7 +137,7 @@ int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t st
 // Pass 2: combine the chunk partials in a fixed order and normalise.
 // Thread t of a block owns channel pair (2t, 2t+1); groups hold an even number of channels.
 // ---------------------------------------------------------------------------------------
-constexpr int GN_TCHUNK = 32;   // tokens per block
+constexpr int GN_TCHUNK = 8;    // tokens per block: many small blocks, every load of a thread in flight at once
 
 __global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* __restrict__ partials,
                                          int T, int C, int groups, int nchunks) {
@@ -143,11 +153,23 @@ __global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* 
     if (cp < npairs) {
         const int g = (2 * cp) / cpg;
         const float shift = bf16_to_f32(xb[g * cpg]);
-        for (int t = t0; t < t1; ++t) {
-            const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
-            const float a = bf16lo_to_f32(pr) - shift, c = bf16hi_to_f32(pr) - shift;
-            s1 += a + c;
-            s2 += a * a + c * c;
+        if (t1 - t0 == GN_TCHUNK) {
+            uint32_t pr[GN_TCHUNK];
+#pragma unroll
+            for (int i = 0; i < GN_TCHUNK; ++i) pr[i] = reinterpret_cast<const uint32_t*>(xb + (size_t)(t0 + i) * C)[cp];
+#pragma unroll
+            for (int i = 0; i < GN_TCHUNK; ++i) {
+                const float a = bf16lo_to_f32(pr[i]) - shift, c = bf16hi_to_f32(pr[i]) - shift;
+                s1 += a + c;
+                s2 += a * a + c * c;
+            }
+        } else {
+            for (int t = t0; t < t1; ++t) {
+                const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
+                const float a = bf16lo_to_f32(pr) - shift, c = bf16hi_to_f32(pr) - shift;
+                s1 += a + c;
+                s2 += a * a + c * c;
+            }
         }
         sh[2 * cp] = s1;
         sh[2 * cp + 1] = s2;
@@ -175,8 +197,8 @@ __global__ __launch_bounds__(64) void groupnorm_finalize_kernel(const uint16_t* 
         a1 += p[0];
         a2 += p[1];
     }
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) { a1 += __shfl_xor(a1, o, 64); a2 += __shfl_xor(a2, o, 64); }
+    a1 = wave_sum(a1);
+    a2 = wave_sum(a2);
     if (lane == 0) {
         const float n = (float)T * (float)cpg;
         const float m1 = a1 / n;
@@ -204,7 +226,7 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
     const float b0 = bf16lo_to_f32(bb), b1 = bf16hi_to_f32(bb);
     const int t0 = chunk * GN_TCHUNK;
     const int t1 = min(T, t0 + GN_TCHUNK);
-#pragma unroll 4
+#pragma unroll 8
     for (int t = t0; t < t1; ++t) {
         const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
         const float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
