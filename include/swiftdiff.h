@@ -149,9 +149,15 @@ int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype,
  *   q   device [Bn, Tq, C] bf16;  k device [Bn, Tk, C] bf16
  *   vt  device [C, Bn * Tkp] bf16: V transposed, sample b's keys at columns
  *       [b*Tkp, b*Tkp + Tk), Tkp = Tk rounded up to a multiple of 8
- *   out device [Bn, Tq, C] bf16 */
+ *   out device [Bn, Tq, C] bf16
+ *   ws  device scratch of sd_attention_workspace_bytes(...) bytes, 256-byte aligned: for
+ *       shapes whose (sample, head, 128-query) tiles would load the CUs unevenly, some
+ *       tiles' key range is halved between two workgroups and their partial results meet
+ *       there.  SD_EWORKSPACE if it is too small. */
+size_t sd_attention_workspace_bytes(int32_t Bn, int32_t Tq, int32_t Tk, int32_t heads);
 int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* vt, uint16_t* out,
-                     int32_t Bn, int32_t Tq, int32_t Tk, int32_t C, int32_t heads, void* stream);
+                     int32_t Bn, int32_t Tq, int32_t Tk, int32_t C, int32_t heads,
+                     void* ws, size_t ws_bytes, void* stream);
 
 /* ---- ff_block_fwd (helper) ------------------------------------------------------------
  * y = x + ff2( geglu( ff1( LN x ) ) );  ff1: [2F, C] with bias, ff2: [C, F] with bias. */

@@ -73,7 +73,8 @@ def _load() -> C.CDLL:
         "sd_attn_block_workspace_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "sd_attn_block_fwd": (C.c_int, [vp, vp, i32, vp, i32, i32, vp, vp, f32, P(sd_proj), P(sd_proj), P(sd_proj), P(sd_proj),
                                         i32, i32, i32, i32, vp, sz, vp]),
-        "sd_attention_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]),
+        "sd_attention_workspace_bytes": (sz, [i32, i32, i32, i32]),
+        "sd_attention_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]),
         "sd_ff_block_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "sd_ff_block_fwd": (C.c_int, [vp, vp, i32, vp, vp, f32, P(sd_proj), P(sd_proj), i32, i32, i32, vp, sz, vp]),
         "sd_groupnorm_workspace_bytes": (sz, [i32, i32, i32, i32]),
@@ -98,7 +99,7 @@ def _load() -> C.CDLL:
 _lib = _load()
 EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32",
            "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
-           "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
+           "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_workspace_bytes", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
            "sd_multi_lora_linear_workspace_bytes", "sd_multi_lora_linear_fwd", "sd_patch_plan_bytes",
@@ -205,11 +206,12 @@ def lora_linear_fwd(x: torch.Tensor, p: Proj, ln_gamma=None, ln_beta=None, ln_ep
     return y
 
 
-def attention_fwd(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, heads: int, out=None) -> torch.Tensor:
+def attention_fwd(q: torch.Tensor, k: torch.Tensor, vt: torch.Tensor, heads: int, out=None, ws=None) -> torch.Tensor:
     Bn, Tq, Cc = q.shape
     Tk = k.shape[1]
     y = out if out is not None else torch.empty_like(q)
-    _check(_lib.sd_attention_fwd(_ptr(q), _ptr(k), _ptr(vt), _ptr(y), Bn, Tq, Tk, Cc, heads, _stream()))
+    w = _ws(_lib.sd_attention_workspace_bytes(Bn, Tq, Tk, heads), ws)
+    _check(_lib.sd_attention_fwd(_ptr(q), _ptr(k), _ptr(vt), _ptr(y), Bn, Tq, Tk, Cc, heads, _ptr(w), w.numel(), _stream()))
     return y
 
 

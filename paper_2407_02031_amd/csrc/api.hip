@@ -143,9 +143,9 @@ static inline int pad8(int v) { return (v + 7) & ~7; }
 // ---------------------------------------------------------------------------------------
 // sub-layers (shared by the single-call entry points and the stack driver)
 // ---------------------------------------------------------------------------------------
-struct AttnWs { uint16_t *n, *q, *k, *vt, *a, *tq, *tk, *tv, *to; };
+struct AttnWs { uint16_t *n, *q, *k, *vt, *a, *tq, *tk, *tv, *to; void* scratch; size_t scratch_bytes; };
 
-static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, int rmax) {
+static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, int rmax, int heads) {
     const size_t M = (size_t)Bn * T, Mk = (size_t)Bn * Tk;
     const size_t r = rmax > 0 ? rmax : 8;
     w.n = (uint16_t*)ws.take(M * C * 2);
@@ -157,6 +157,9 @@ static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, i
     w.tk = (uint16_t*)ws.take(Mk * r * 2);
     w.tv = (uint16_t*)ws.take(Mk * r * 2);
     w.to = (uint16_t*)ws.take(M * r * 2);
+    // sized for the larger of the two key counts the sub-layer is used with (Tk here, T for self-attention)
+    w.scratch_bytes = std::max(attention_scratch_bytes(Bn, T, Tk, heads), attention_scratch_bytes(Bn, T, T, heads));
+    w.scratch = ws.take(w.scratch_bytes);
     return ws.ok();
 }
 
@@ -182,7 +185,7 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV))) return rc;
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
-    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, stream);
+    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, w.scratch, w.scratch_bytes, stream);
     timing_mark(atag, 1, stream);
     if (rc) return rc;
     ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
@@ -313,15 +316,24 @@ extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj*
 // ---------------------------------------------------------------------------------------
 // attention_fwd / attn_block_fwd
 // ---------------------------------------------------------------------------------------
+extern "C" size_t sd_attention_workspace_bytes(int32_t Bn, int32_t Tq, int32_t Tk, int32_t heads) {
+    return attention_scratch_bytes(Bn, Tq, Tk, heads) + 256;
+}
+
 extern "C" int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* vt, uint16_t* out, int32_t Bn,
-                                int32_t Tq, int32_t Tk, int32_t C, int32_t heads, void* stream) {
+                                int32_t Tq, int32_t Tk, int32_t C, int32_t heads, void* ws, size_t ws_bytes, void* stream) {
     SD_REQUIRE(Bn >= 0 && Tq >= 0 && Tk >= 0 && heads > 0, SD_EINVAL, "attention: Bn=%d Tq=%d Tk=%d heads=%d", Bn, Tq, Tk, heads);
     SD_REQUIRE(C == heads * 64, SD_EUNSUPPORTED, "attention: C=%d heads=%d (head dim must be 64)", C, heads);
     if (Bn == 0 || Tq == 0) return SD_OK;
     SD_REQUIRE(Tk >= 1, SD_EINVAL, "attention: no keys");
     SD_REQUIRE(aligned16(q) && aligned16(k) && aligned16(vt) && aligned16(out), SD_EINVAL, "attention: pointers must be 16-byte aligned");
     const int Tkp = pad8(Tk);
-    return launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, static_cast<hipStream_t>(stream));
+    const size_t need = attention_scratch_bytes(Bn, Tq, Tk, heads);
+    Workspace w(ws, ws_bytes);
+    void* scratch = need ? w.take(need) : nullptr;
+    SD_REQUIRE(need == 0 || (ws && w.ok()), SD_EWORKSPACE, "attention: workspace of %zu bytes, need %zu", ws_bytes,
+               sd_attention_workspace_bytes(Bn, Tq, Tk, heads));
+    return launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, scratch, need, static_cast<hipStream_t>(stream));
 }
 
 extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max) {
@@ -329,7 +341,7 @@ extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C
     if (Bn <= 0 || T <= 0 || C <= 0) return 256;
     Workspace ws((void*)256, (size_t)-1 / 2);
     AttnWs w;
-    carve_attn(ws, w, Bn, T, C, Tc > 0 ? (Tc > T ? Tc : T) : T, r_max);
+    carve_attn(ws, w, Bn, T, C, Tc > 0 ? (Tc > T ? Tc : T) : T, r_max, C / 64);
     return ws.used;
 }
 
@@ -355,7 +367,7 @@ extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const
     const int Tk = ctx ? Tc : T;
     Workspace w(ws, ws_bytes);
     AttnWs aw;
-    SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax), SD_EWORKSPACE, "attn_block: workspace of %zu bytes is too small", ws_bytes);
+    SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax, heads), SD_EWORKSPACE, "attn_block: workspace of %zu bytes is too small", ws_bytes);
     return attn_sublayer(x, y, io_dtype == SD_F32, ctx, Tc, Dc, ln_gamma, ln_beta, ln_eps, *q, *k, *v, *o, Bn, T, C, heads, aw,
                          static_cast<hipStream_t>(stream));
 }
@@ -418,7 +430,7 @@ static bool carve_stack(Workspace& ws, StackWs& w, int Bn, int T, int C, int Tc,
     w.h = (float*)ws.take(M * C * 4);
     w.g = (uint16_t*)ws.take(M * C * 2);
     w.gn = (float*)ws.take(groupnorm_partials_bytes(Bn, T, 32));
-    carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax);
+    carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax, C / 64);
     carve_ff(ws, w.f, (int)M, C, 4 * C, rmax);
     return ws.ok();
 }

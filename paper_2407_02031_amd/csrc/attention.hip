@@ -16,6 +16,14 @@
 // of every 16-key group in the order [0-3, 8-11, 4-7, 12-15]: the score accumulator of a
 // lane then holds 8 consecutive keys per 16-key group, and the matching V^T operand is a
 // single 16-byte LDS read of the plain [C, keys] layout.
+//
+// Work split.  A (sample, head, 128-query tile) is a tile; a workgroup normally takes one.
+// When the tile count lies between two and three per CU (640 tiles on 256 CUs leaves half
+// the CUs with three tiles and half with two), the launch is padded to exactly three
+// workgroups per CU by cutting the key range of the surplus tiles in half: every CU then
+// holds two whole tiles and one half.  The two halves of a cut tile leave their unnormalised
+// accumulator, running maximum and row sum in a scratch buffer; a second, small kernel merges
+// them.
 #include "common.hpp"
 
 namespace sd {
@@ -43,23 +51,67 @@ __device__ __forceinline__ void attn_wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+constexpr int PART_FLOATS = 34 * 256;   // one half of a cut tile: 32 accumulator values, max, sum per thread
+
+// normalise and store one 32-query block of a tile: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
+__device__ __forceinline__ void store_queries(const f32x16 (&o)[2], float l, uint16_t* __restrict__ out, int64_t ldo,
+                                              int b, int Tq, int row, int head, int hi) {
+    float l_lo, l_hi;
+    both_halves(l, l_lo, l_hi);   // the two half-wavefronts summed different keys of the same query
+    const float inv = 1.0f / (l_lo + l_hi);
+    if (row < Tq) {
+        uint16_t* op = out + ((int64_t)b * Tq + row) * ldo + head * 64 + 4 * hi;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                bf16x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[db][4 * v4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * v4) = w;
+            }
+    }
+}
+
+// nsplit == 0: workgroup i takes tile i.  Otherwise the grid holds nfull whole tiles and
+// 2 * nsplit half tiles (both multiples of 8), dealt so that each XCD, and in dispatch order
+// each CU, first receives its share of whole tiles and then its share of halves.
 template <int QB>
-__global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
+__global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
                                                         const uint16_t* __restrict__ k, int64_t ldk,
                                                         const uint16_t* __restrict__ vt, int64_t ldvt,
                                                         uint16_t* __restrict__ out, int64_t ldo,
-                                                        int Tq, int Tk, int Tkp, int heads, int qtiles, float c) {
+                                                        int Tq, int Tk, int Tkp, int heads, int qtiles, float c,
+                                                        int nfull, int nsplit, float* __restrict__ parts) {
+    static_assert(QB == 1, "one 32-query block per wavefront");
     constexpr int BQ = 4 * 32 * QB;
     __shared__ u32x4 ldsK[2][64 * 8];   // [key (permuted within 16)][8 chunks of 8 d], 2-deep ring
     __shared__ u32x4 ldsV[3][64 * 8];   // [d][8 chunks of 8 keys], 3-deep ring
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of
     // (sample, head, query tile) so that one head's K and V stay in one XCD's L2.
-    const int total = gridDim.x;
-    int wi = blockIdx.x;
-    if ((total & 7) == 0) wi = (wi & 7) * (total >> 3) + (wi >> 3);
-    const int qt = wi % qtiles;
-    const int head = (wi / qtiles) % heads, b = wi / (qtiles * heads);
+    const int nt = (Tk + 63) >> 6;
+    int tile, s0 = 0, s1 = nt, part = -1;   // steps [s0, s1) of the tile; part >= 0: a half tile
+    if (nsplit == 0) {
+        const int total = gridDim.x;
+        tile = blockIdx.x;
+        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
+    } else {
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+        const int fpx = nfull >> 3, hpx = nsplit >> 2;   // whole tiles / halves per XCD
+        if (j < fpx) {
+            tile = xcd * fpx + j;
+        } else {
+            const int h = xcd * hpx + (j - fpx);
+            tile = nfull + (h >> 1);
+            part = h & 1;
+            const int mid = (nt + 1) >> 1;
+            s0 = part ? mid : 0;
+            s1 = part ? nt : mid;
+        }
+    }
+    const int qt = tile % qtiles;
+    const int head = (tile / qtiles) % heads, b = tile / (qtiles * heads);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
@@ -97,7 +149,6 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     }
     const char* vbase = reinterpret_cast<const char*>(vt + (int64_t)(head * 64) * ldvt + (int64_t)b * Tkp);
     const bool ragged = (Tk & 63) != 0;
-    const int nt = (Tk + 63) >> 6;
     auto issue_kv = [&](int t, int kslot, int vslot) {
         const int key0 = t * 64;
         const uint32_t kdst = ldsK_base + (uint32_t)(kslot * 8192 + wave * 1024);
@@ -270,10 +321,10 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
                 }
     };
 
-    // ---- prologue: tiles 0 and 1 in flight, S of tile 0
-    issue_kv(0, 0, 0);
-    if (nt > 1) {
-        issue_kv(1, 1, 1);
+    // ---- prologue: the first two key tiles in flight, S of the first
+    issue_kv(s0, s0 & 1, 0);
+    if (s0 + 1 < s1) {
+        issue_kv(s0 + 1, (s0 + 1) & 1, 1);
         attn_wait_vmcnt<4>();
     } else {
         attn_wait_vmcnt<0>();
@@ -282,8 +333,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     f32x16 sa[QB][2], sb[QB][2];
     {
         bf16x8 kf0[2][2];
-        load_kfrags(0, 0, kf0);
-        compute_s(0, sa, kf0);
+        load_kfrags(s0, 0, kf0);
+        compute_s(s0, sa, kf0);
     }
 
     // ---- main loop, software-pipelined: the score MFMAs of tile t+1 are independent of the
@@ -300,7 +351,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         attn_wait_vmcnt<0>();
         __syncthreads();
         const int vnext2 = vslot == 0 ? 2 : vslot - 1;   // (vslot + 2) % 3
-        if (t + 2 < nt) issue_kv(t + 2, t & 1, vnext2);
+        if (t + 2 < s1) issue_kv(t + 2, t & 1, vnext2);
         bf16x8 kf0[2][2];
         load_kfrags(t + 1, 0, kf0);
         __builtin_amdgcn_sched_barrier(0);
@@ -310,55 +361,98 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
         accumulate_o(vslot, pf);
         vslot = vslot == 2 ? 0 : vslot + 1;
     };
-    int t = 0;
+    const bool mask_last = ragged && s1 == nt;
+    int t = s0;
 #pragma unroll 1
-    for (; t + 2 < nt; t += 2) {
+    for (; t + 2 < s1; t += 2) {
         step(t, sa, sb);
         step(t + 1, sb, sa);
     }
-    if (t + 1 < nt) {            // one more pipelined step, last tile's scores end up in sb
+    if (t + 1 < s1) {            // one more pipelined step, last tile's scores end up in sb
         step(t, sa, sb);
-        if (ragged) mask_tail(nt - 1, sb);
+        if (mask_last) mask_tail(nt - 1, sb);
         update_max(sb);
         exponentials(sb, pf);
     } else {                     // last tile's scores are in sa
-        if (ragged) mask_tail(nt - 1, sa);
+        if (mask_last) mask_tail(nt - 1, sa);
         update_max(sa);
         exponentials(sa, pf);
     }
     // the last tile's V^T landed before the barrier of the step before (or of the prologue)
-    if (Tk & 7) {
+    if ((Tk & 7) && s1 == nt) {
         zero_pad_keys(nt - 1, vslot);
         __syncthreads();
     }
     accumulate_o(vslot, pf);
 
-    // ---- normalise and store: lane holds query l32, d = db*32 + 8*(v/4) + 4*hi + v%4
+    // ---- a whole tile is normalised and stored; half of a cut tile leaves its state behind
+    if (part < 0) {
+        store_queries(o[0], l[0], out, ldo, b, Tq, q0 + l32, head, hi);
+    } else {
+        float* pp = parts + ((size_t)(tile - nfull) * 2 + part) * PART_FLOATS + tid;
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) {
-        float l_lo, l_hi;
-        both_halves(l[qb], l_lo, l_hi);   // the two half-wavefronts summed different keys of the same query
-        const float lt = l_lo + l_hi;
-        const float inv = 1.0f / lt;
-        const int row = q0 + qb * 32 + l32;
-        if (row < Tq) {
-            uint16_t* op = out + ((int64_t)b * Tq + row) * ldo + head * 64 + 4 * hi;
+        for (int db = 0; db < 2; ++db)
 #pragma unroll
-            for (int db = 0; db < 2; ++db)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    bf16x4 w;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) w[e] = (__bf16)(o[qb][db][4 * v4 + e] * inv);
-                    *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * v4) = w;
-                }
-        }
+            for (int v = 0; v < 16; ++v) pp[(db * 16 + v) * 256] = o[0][db][v];
+        pp[32 * 256] = m[0];
+        pp[33 * 256] = l[0];
     }
+}
+
+// One workgroup per cut tile: combine the two halves about their common maximum.
+__global__ __launch_bounds__(256) void attention_merge_kernel(const float* __restrict__ parts, uint16_t* __restrict__ out, int64_t ldo,
+                                                              int Tq, int heads, int qtiles, int nfull, float c) {
+    const int tile = nfull + blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const float* pa = parts + ((size_t)blockIdx.x * 2) * PART_FLOATS + tid;
+    const float* pb = pa + PART_FLOATS;
+    const float ma = pa[32 * 256], mb = pb[32 * 256];
+    const float mm = fmaxf(ma, mb);
+    const float fa = __builtin_amdgcn_exp2f((ma - mm) * c), fb = __builtin_amdgcn_exp2f((mb - mm) * c);
+    f32x16 o[2];
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = pa[(db * 16 + v) * 256] * fa + pb[(db * 16 + v) * 256] * fb;
+    const float l = pa[33 * 256] * fa + pb[33 * 256] * fb;
+    const int qt = tile % qtiles;
+    const int head = (tile / qtiles) % heads, b = tile / (qtiles * heads);
+    store_queries(o, l, out, ldo, b, Tq, qt * 128 + wave * 32 + l32, head, hi);
+}
+
+// CUs of the current device (cached; the query allocates nothing)
+static int device_cus() {
+    static int cus[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cus[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev] = n;
+    }
+    return cus[dev];
+}
+
+// number of tiles to cut in half (0: one workgroup per tile)
+static int attention_nsplit(int Bn, int Tq, int Tk, int heads) {
+    const long tiles = (long)((Tq + 127) / 128) * heads * Bn;
+    const int nt = (Tk + 63) / 64;
+    const long cus = device_cus();
+    if (nt < 8 || tiles <= 2 * cus || tiles >= 3 * cus) return 0;
+    const long nsplit = 3 * cus - tiles, nfull = tiles - nsplit;
+    if (nfull <= 0 || (nfull & 7) || (nsplit & 3)) return 0;
+    return (int)nsplit;
+}
+
+size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads) {
+    if (Bn <= 0 || Tq <= 0 || Tk <= 0 || heads <= 0) return 0;
+    return (size_t)attention_nsplit(Bn, Tq, Tk, heads) * 2 * PART_FLOATS * sizeof(float);
 }
 
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
-                     int Bn, int Tq, int Tk, int Tkp, int heads, hipStream_t stream) {
+                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, hipStream_t stream) {
     SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
     SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
     SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
@@ -366,8 +460,19 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     if (Bn <= 0 || Tq <= 0 || heads <= 0) return SD_OK;
     const float c = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
     const int qtiles = (Tq + 127) / 128;
-    dim3 grid((unsigned)(qtiles * heads * Bn));
-    hipLaunchKernelGGL(attention_kernel<1>, grid, dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo, Tq, Tk, Tkp, heads, qtiles, c);
+    const long tiles = (long)qtiles * heads * Bn;
+    SD_REQUIRE(tiles < (1l << 30), SD_EINVAL, "attention: problem too large");
+    int nsplit = attention_nsplit(Bn, Tq, Tk, heads);
+    const size_t need = (size_t)nsplit * 2 * PART_FLOATS * sizeof(float);
+    if (nsplit > 0 && !(scratch && scratch_bytes >= need && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0)) nsplit = 0;
+    const int nfull = (int)tiles - nsplit;
+    hipLaunchKernelGGL(attention_kernel<1>, dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo,
+                       Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
+    if (nsplit > 0) {
+        SD_HIP_CHECK(hipGetLastError());
+        hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)nsplit), dim3(256), 0, stream, static_cast<const float*>(scratch), out, ldo,
+                           Tq, heads, qtiles, nfull, c);
+    }
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }

@@ -145,8 +145,11 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
                      int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream);
 size_t groupnorm_partials_bytes(int Bn, int T, int groups);
 
+// scratch: attention_scratch_bytes(...) bytes, 16-byte aligned, for the launches that cut
+// some tiles' key range in half (without it every workgroup takes one whole tile)
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
-                     int Bn, int Tq, int Tk, int Tkp, int heads, hipStream_t stream);
+                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, hipStream_t stream);
+size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads);
 
 }  // namespace sd

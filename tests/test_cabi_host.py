@@ -93,11 +93,11 @@ def test_forward_calls_reject_bad_arguments_before_touching_the_device(B):
     # GEGLU with residual
     assert L.sd_lora_linear_fwd(0x1000, 0, C.byref(p), None, None, 1e-5, 0x7000, 0x2000, 0, 1, 4, 8, 8, 0x3000, 1 << 20, None) == -1
     # head dim != 64
-    assert L.sd_attention_fwd(0x1000, 0x2000, 0x3000, 0x4000, 2, 16, 16, 96, 2, None) == -2
+    assert L.sd_attention_fwd(0x1000, 0x2000, 0x3000, 0x4000, 2, 16, 16, 96, 2, None, 0, None) == -2
     assert b"head dim" in L.sd_last_error()
     # empty problems succeed without a device
     assert L.sd_lora_linear_fwd(None, 0, C.byref(p), None, None, 1e-5, None, None, 0, 0, 0, 8, 8, None, 0, None) == 0
-    assert L.sd_attention_fwd(None, None, None, None, 0, 0, 0, 64, 1, None) == 0
+    assert L.sd_attention_fwd(None, None, None, None, 0, 0, 0, 64, 1, None, 0, None) == 0
     assert L.sd_lora_patch(None, 0, 0, None) == 0
     # multi-LoRA: segments must cover [0, M)
     so = (C.c_int32 * 2)(0, 5)

@@ -138,6 +138,28 @@ def test_attention_matches_oracle(B, Bn, Tq, Tk, heads, qscale):
         assert rel_err(O.attention(q, k, np.roll(v, 1, axis=1), heads), ref) > 10 * BF16_TOL
 
 
+def test_attention_cut_tiles(B):
+    """640 query tiles on a 256-CU part: the launch cuts the key range of 128 tiles in half and
+    merges the halves afterwards (odd number of key tiles, ragged last one, peaky scores so the
+    two halves of a tile end with different running maxima)."""
+    Bn, Tq, Tk, heads = 1, 4096, 520, 20
+    r = rng(4096 + 520)
+    C = heads * 64
+    q = G.bf16_round((2.0 * r.standard_normal((Bn, Tq, C))).astype(np.float32))
+    k = G.bf16_round(r.standard_normal((Bn, Tk, C)).astype(np.float32))
+    v = G.bf16_round(r.standard_normal((Bn, Tk, C)).astype(np.float32))
+    k[:, 100] *= 4.0
+    k[:, Tk - 2] *= 4.0
+    assert B.lib().sd_attention_workspace_bytes(Bn, Tq, Tk, heads) > 256   # this shape does take the cut path
+    ref = O.attention(q, k, v, heads)
+    got = host(B.attention_fwd(dev(q, B), dev(k, B), vt_layout(v, B), heads))
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) <= BF16_TOL
+    # per query tile too: a wrong merge of one cut tile must not hide behind the global maximum
+    per_tile = np.abs(got - ref).reshape(Bn, Tq // 128, 128, C).max(axis=(2, 3)) / np.abs(ref).max()
+    assert per_tile.max() <= BF16_TOL
+
+
 def test_attention_large_scores_in_alternate_key_octets(B):
     """Keys whose index has bit 3 set score ~+770, the others ~-770: a running maximum taken
     over only part of a tile's keys would overflow the exponentials (the kernel holds the two
