@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 # HBM bytes per lora_patch launch on the 310-matrix sweep, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this file, each scaled by the same counter's reading on a pure copy of
 # known size (lora_unpatch): see profiles/lora_patch_hbm_traffic.txt
-PATCH_TRAFFIC_BYTES = 10.5e9
+PATCH_TRAFFIC_BYTES = 10.64e9   # FETCH_SIZE + WRITE_SIZE per patch launch, scaled (profiles/lora_patch_hbm_traffic.txt)
 
 
 def stack_flops(cfg) -> float:

@@ -185,9 +185,11 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV))) return rc;
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
-    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, w.scratch, w.scratch_bytes, stream);
+    int cut = 0;
+    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, w.scratch, w.scratch_bytes, &cut, stream);
     timing_mark(atag, 1, stream);
     if (rc) return rc;
+    if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, cut, stream))) return rc;
     ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
     return run_projections(&oc, 1, stream, SD_TIMING_ATTN_OUT);
 }
@@ -333,7 +335,11 @@ extern "C" int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint
     void* scratch = need ? w.take(need) : nullptr;
     SD_REQUIRE(need == 0 || (ws && w.ok()), SD_EWORKSPACE, "attention: workspace of %zu bytes, need %zu", ws_bytes,
                sd_attention_workspace_bytes(Bn, Tq, Tk, heads));
-    return launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, scratch, need, static_cast<hipStream_t>(stream));
+    int cut = 0;
+    const int rc = launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, scratch, need, &cut,
+                                    static_cast<hipStream_t>(stream));
+    if (rc) return rc;
+    return launch_attention_merge(scratch, out, C, Bn, Tq, heads, cut, static_cast<hipStream_t>(stream));
 }
 
 extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max) {

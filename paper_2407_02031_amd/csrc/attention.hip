@@ -452,11 +452,13 @@ size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads) {
 
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
-                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, hipStream_t stream) {
+                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, int* cut_tiles,
+                     hipStream_t stream) {
     SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
     SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
     SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
     SD_REQUIRE(ldk > 0 && ldvt > 0 && ldk < (1 << 23) && ldvt < (1 << 23), SD_EINVAL, "attention: leading dimensions out of range");
+    *cut_tiles = 0;
     if (Bn <= 0 || Tq <= 0 || heads <= 0) return SD_OK;
     const float c = 0.125f * 1.44269504088896340736f;   // 1/sqrt(64) * log2(e)
     const int qtiles = (Tq + 127) / 128;
@@ -468,11 +470,18 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     const int nfull = (int)tiles - nsplit;
     hipLaunchKernelGGL(attention_kernel<1>, dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo,
                        Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
-    if (nsplit > 0) {
-        SD_HIP_CHECK(hipGetLastError());
-        hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)nsplit), dim3(256), 0, stream, static_cast<const float*>(scratch), out, ldo,
-                           Tq, heads, qtiles, nfull, c);
-    }
+    SD_HIP_CHECK(hipGetLastError());
+    *cut_tiles = nsplit;
+    return SD_OK;
+}
+
+int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, int cut_tiles, hipStream_t stream) {
+    if (cut_tiles <= 0) return SD_OK;
+    const float c = 0.125f * 1.44269504088896340736f;
+    const int qtiles = (Tq + 127) / 128;
+    const int nfull = qtiles * heads * Bn - cut_tiles;
+    hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)cut_tiles), dim3(256), 0, stream, static_cast<const float*>(scratch), out, ldo,
+                       Tq, heads, qtiles, nfull, c);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
