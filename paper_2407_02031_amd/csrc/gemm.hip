@@ -435,6 +435,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     bool geglu = g.p[0].geglu_F > 0;
     bool guard = false;
     int maxN = 0;
+    long t128 = 0;        // workgroup tiles at 128x128
     bool res32 = false;   // some problem adds an fp32 residual: take the kernel that prefetches it
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
@@ -453,6 +454,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (P.Mp == 0 || P.N == 0) continue;
         if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
         if (P.N > maxN) maxN = P.N;
+        t128 += (long)((P.Mp + 127) / 128) * ((P.N + 127) / 128);
     }
     // drop empty problems
     int w = 0;
@@ -460,15 +462,23 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (g.p[i].Mp > 0 && g.p[i].N > 0) { if (w != i) g.p[w] = g.p[i]; ++w; }
     g.n = w;
     if (w == 0) return SD_OK;
-    // Tile choice.  Measured on MI355X the operand stream (direct-to-LDS loads out of L2) and
-    // not the MFMA rate bounds these GEMMs; 128x128x64 tiles with a 2-stage ring (64 KB, two
-    // workgroups per CU so one workgroup's prologue and epilogue overlap the other's main
-    // loop) beat 256x128 tiles at every shape of the transformer block.  Down-projections
-    // (N = rank <= 64) use 64x64 tiles with a 5-stage ring.
-    if (geglu) return launch_cfg<128, 128, 64, 2, 2, 2, true, false>(g, guard, stream);
+    // Tile choice, from timing whole transformer-block steps with each variant on one machine.
+    // What pays is wavefronts in flight per CU, not operand reuse: these GEMMs wait on the
+    // L2 -> LDS operand stream and on their own prologues and epilogues, and 256x128, 128x160
+    // (one exact round) and 3-stage variants all lost.  Launches of fewer than 1024 tiles at
+    // 128x128 (everything in the block except the feed-forward in-projection) run 64x128 tiles,
+    // 4 waves, 48 KB of LDS, three workgroups per CU; larger ones run 128x128 tiles with 8 waves
+    // of 32x64, two workgroups per CU.  Down-projections (N = rank <= 64): 64x64 tiles, 5-stage
+    // ring.
     if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false, false>(g, guard, stream);
-    if (res32) return launch_cfg<128, 128, 64, 2, 2, 2, false, true>(g, guard, stream);
-    return launch_cfg<128, 128, 64, 2, 2, 2, false, false>(g, guard, stream);
+    if (t128 < 1024) {
+        if (geglu) return launch_cfg<64, 128, 64, 2, 2, 2, true, false>(g, guard, stream);
+        if (res32) return launch_cfg<64, 128, 64, 2, 2, 2, false, true>(g, guard, stream);
+        return launch_cfg<64, 128, 64, 2, 2, 2, false, false>(g, guard, stream);
+    }
+    if (geglu) return launch_cfg<128, 128, 64, 4, 2, 2, true, false>(g, guard, stream);
+    if (res32) return launch_cfg<128, 128, 64, 4, 2, 2, false, true>(g, guard, stream);
+    return launch_cfg<128, 128, 64, 4, 2, 2, false, false>(g, guard, stream);
 }
 
 }  // namespace sd
