@@ -29,6 +29,14 @@ GroupNorm + proj_in and proj_out + input) is the standard SDXL spatial transform
 the paper prints no shapes or formulas for it, so those parts are pinned by the
 mathematical properties listed in tests/test_oracle_pins.py, not by paper values.
 
+  * Section 3.1 (add-on usage table) and Section 4.2: a request carries one or two
+    LoRAs, loaded in parallel and each merged into the base weights; several adapters
+    on one matrix are the sum of their products, W' = W + sum_i scale_i * B_i @ A_i.
+  * Section 2, "Diffusion model inference": the conditionally and unconditionally
+    denoised latents of a step are combined by a weighted sum (classifier-free
+    guidance); the paper cites the guidance formula eps_u + g * (eps_c - eps_u) and
+    prints no weights, so g is an argument.
+
 Parity pins: linear / lora_linear / layernorm / groupnorm / attention / gelu / geglu /
 lora_patch / multi_lora_linear are pinned by brute-force loops, closed forms and
 invariants.  `block` and `spatial_transformer` are compositions with no closed form:
@@ -232,6 +240,45 @@ def lora_patch(W, A, B, scale):
     delta = (np.asarray(B, np.float32) @ np.asarray(A, np.float32)).astype(np.float32)
     delta = (np.float32(scale) * delta).astype(np.float32)
     return (W + delta).astype(np.float32), W.copy()
+
+
+def bf16_rne(x):
+    """float32 -> nearest bfloat16 (ties to even), returned widened to float32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    return (u.astype(np.uint32) << 16).view(np.float32).reshape(np.shape(x))
+
+
+def lora_patch_multi(W, adapters, serving=False):
+    """Several adapters merged into one matrix in one pass (Section 4.2; one or two LoRAs
+    per request, Section 3.1): the adapters are applied one after the other, each with
+    the rounding chain of `lora_patch`,
+        W_0 = W,  W_i = fl32(W_{i-1} + fl32(scale_i * fl32(B_i @ A_i))),  W' = W_n,
+    so a single pass over W equals n successive single patches bit for bit.  `undo` is
+    W's bits before the first adapter.  With serving=True also returns the bfloat16
+    copy of W' (round to nearest even) that the bf16 GEMMs read, widened to float32.
+    `adapters` is a sequence of (A [r_i, in], B [out, r_i], scale_i).
+    """
+    W0 = np.asarray(W, dtype=np.float32)
+    cur = W0
+    for A, B, scale in adapters:
+        cur, _ = lora_patch(cur, A, B, scale)
+    if serving:
+        return cur, W0.copy(), bf16_rne(cur)
+    return cur, W0.copy()
+
+
+def cfg_combine(eps_uncond, eps_cond, guidance, out_bf16=True):
+    """Classifier-free-guidance weighted sum of the two denoised latents of a step
+    (Section 2, "Diffusion model inference"): eps = eps_u + g * (eps_c - eps_u), formed
+    in float32 from the (bfloat16-representable) inputs as
+    fl32(eps_u + fl32(g * fl32(eps_c - eps_u))), then rounded to bfloat16 if asked."""
+    eu = np.asarray(eps_uncond, dtype=np.float32)
+    ec = np.asarray(eps_cond, dtype=np.float32)
+    d = (ec - eu).astype(np.float32)
+    d = (np.float32(guidance) * d).astype(np.float32)
+    out = (eu + d).astype(np.float32)
+    return bf16_rne(out) if out_bf16 else out
 
 
 def lora_unpatch(W_patched, undo):

@@ -7,6 +7,7 @@ import math
 import numpy as np
 import pytest
 
+from conftest import rel_err
 from oracle import sdxl_block_oracle as O
 from workloads import sdxl_inputs as G
 
@@ -333,6 +334,79 @@ def test_subtraction_does_not_restore_the_weights():
 
 
 # ------------------------------------------------------------ input generator
+def test_patch_multi_is_successive_single_patches_and_exact_on_integers():
+    r = np.random.default_rng(11)
+    out_f, in_f = 6, 5
+    W = r.integers(-8, 9, size=(out_f, in_f)).astype(np.float32)
+    ads = [(r.integers(-3, 4, size=(rk, in_f)).astype(np.float32), r.integers(-3, 4, size=(out_f, rk)).astype(np.float32), sc)
+           for rk, sc in ((2, 1.0), (3, 2.0), (1, -1.0))]
+    Wp, undo = O.lora_patch_multi(W, ads)
+    # integers: every intermediate is exact, so the plain definition W + sum_i s_i B_i A_i by loops
+    for n in range(out_f):
+        for k in range(in_f):
+            acc = float(W[n, k])
+            for A, B, sc in ads:
+                acc += sc * sum(float(B[n, j]) * float(A[j, k]) for j in range(A.shape[0]))
+            assert Wp[n, k] == acc
+    assert undo.tobytes() == W.tobytes()
+    # one adapter: the single-patch function, bit for bit
+    W1, _ = O.lora_patch(W, *ads[0])
+    assert O.lora_patch_multi(W, ads[:1])[0].tobytes() == W1.tobytes()
+    # real-valued: equals successive single patches bit for bit, and the fp64 sum within 1e-6
+    Wr = (0.02 * r.standard_normal((40, 24))).astype(np.float32)
+    adr = [((0.02 * r.standard_normal((rk, 24))).astype(np.float32), (0.02 * r.standard_normal((40, rk))).astype(np.float32), sc)
+           for rk, sc in ((8, 1.0), (4, 0.5))]
+    Wm, _ = O.lora_patch_multi(Wr, adr)
+    step = Wr
+    for A, B, sc in adr:
+        step, _ = O.lora_patch(step, A, B, sc)
+    assert Wm.tobytes() == step.tobytes()
+    ref = Wr.astype(np.float64) + sum(sc * (B.astype(np.float64) @ A.astype(np.float64)) for A, B, sc in adr)
+    assert rel_err(Wm, ref) <= 1e-6
+    # dropping an adapter or its scale is visible
+    assert rel_err(O.lora_patch_multi(Wr, adr[:1])[0], ref) > 1e-4
+    assert rel_err(O.lora_patch_multi(Wr, [adr[0], (adr[1][0], adr[1][1], 1.0)])[0], ref) > 1e-4
+
+
+def test_bf16_rounding_of_the_serving_copy():
+    import torch
+    # ties go to the even mantissa; one ulp above the tie goes up
+    cases = {0x3F808000: 0x3F80, 0x3F818000: 0x3F82, 0x3F808001: 0x3F81, 0xBF808000: 0xBF80, 0x3F7FFFFF: 0x3F80, 0x00000000: 0x0000}
+    for bits, want in cases.items():
+        x = np.array([bits], dtype=np.uint32).view(np.float32)
+        got = O.bf16_rne(x).view(np.uint32)[0] >> 16
+        assert got == want, (hex(bits), hex(got), hex(want))
+    r = np.random.default_rng(5)
+    x = (r.standard_normal(4096) * np.exp(r.uniform(-20, 20, 4096))).astype(np.float32)
+    lib = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()      # an independent implementation
+    assert O.bf16_rne(x).tobytes() == lib.tobytes()
+    Wr = (0.02 * r.standard_normal((16, 8))).astype(np.float32)
+    A, B = (0.02 * r.standard_normal((4, 8))).astype(np.float32), (0.02 * r.standard_normal((16, 4))).astype(np.float32)
+    Wp, undo, Wb = O.lora_patch_multi(Wr, [(A, B, 1.0)], serving=True)
+    assert Wb.tobytes() == O.bf16_rne(Wp).tobytes() and np.abs(Wb - Wp).max() <= np.abs(Wp).max() * 2.0 ** -8
+
+
+def test_cfg_combine_special_cases():
+    r = np.random.default_rng(9)
+    eu = G.bf16_round(r.standard_normal((4, 33)).astype(np.float32))
+    ec = G.bf16_round(r.standard_normal((4, 33)).astype(np.float32))
+    assert O.cfg_combine(eu, ec, 0.0).tobytes() == eu.tobytes()          # g = 0: the unconditional latent
+    assert O.cfg_combine(eu, ec, 1.0, out_bf16=False).tobytes() == (eu + (ec - eu)).astype(np.float32).tobytes()
+    assert np.abs(O.cfg_combine(eu, ec, 1.0) - ec).max() <= np.abs(ec).max() * 2.0 ** -7   # g = 1: the conditional one
+    g = 7.5
+    out = O.cfg_combine(eu, ec, g, out_bf16=False)
+    for i in range(4):
+        for j in range(33):
+            want = float(eu[i, j]) + g * (float(ec[i, j]) - float(eu[i, j]))
+            assert abs(float(out[i, j]) - want) <= 1e-6 * max(1.0, abs(want))
+    # the two latents are not interchangeable, and the weight is not dropped
+    assert rel_err(O.cfg_combine(ec, eu, g, out_bf16=False), out) > 0.1
+    assert rel_err(O.cfg_combine(eu, ec, 1.0, out_bf16=False), out) > 0.1
+    # exact on small integers
+    eu_i = np.array([[1.0, -2.0, 3.0]], np.float32); ec_i = np.array([[2.0, 2.0, -1.0]], np.float32)
+    assert O.cfg_combine(eu_i, ec_i, 3.0, out_bf16=False).tolist() == [[4.0, 10.0, -9.0]]
+
+
 def test_bf16_helpers_roundtrip_and_rne():
     bits = np.arange(0, 0x7F80, 7, dtype=np.uint16)          # positive finite bf16 values
     assert np.array_equal(G.bf16_bits(G.bf16_widen(bits)), bits)
