@@ -232,8 +232,37 @@ def main() -> int:
                         "roofline": {"kernel": "lora_patch_kernel", "bound": "hbm", "achieved": round(pbytes / (pms * 1e-3) / 1e9, 1),
                                      "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(pbytes / (pms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                      "algorithmic_bytes": pbytes, "traffic": PATCH_TRAFFIC_BYTES}}
-        del mats, plan
+        # two adapters per matrix in one pass, with the bf16 serving copy (the production norm is
+        # one or two LoRAs per request): W read once, W', undo and the bf16 copy written once
+        multi = []
+        for (Wt, At, Bt, Ut, sc) in mats:
+            A2 = torch.randn(At.shape, device="cuda", generator=gen) * 0.02
+            B2 = torch.randn(Bt.shape, device="cuda", generator=gen) * 0.02
+            multi.append((Wt, Ut, torch.empty(Wt.shape, dtype=torch.bfloat16, device="cuda"), [(At, Bt, sc), (A2, B2, sc)]))
+        mplan = B.PatchMultiPlan(multi)
+        for _ in range(2):
+            B.lora_patch_multi(mplan)
+            B.lora_unpatch_multi(mplan)
+        mt, mu = [], []
+        for _ in range(6):
+            mt += time_events(lambda: B.lora_patch_multi(mplan), 1)
+            mu += time_events(lambda: B.lora_unpatch_multi(mplan), 1)
+        mms, mus = float(np.mean(mt)), float(np.mean(mu))
+        mbytes = elems * 14.0 + 2 * ab * 4.0
+        out["patch_multi"] = {"workload": "patch_sweep_310_matrices_2_adapters_r32_fp32_plus_bf16_serving_copy",
+                              "patch_ms": round(mms, 4), "patch_gbs": round(mbytes / (mms * 1e-3) / 1e9, 1),
+                              "patch_frac_of_hbm": round(mbytes / (mms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                              "unpatch_ms": round(mus, 4), "unpatch_gbs": round(elems * 10.0 / (mus * 1e-3) / 1e9, 1),
+                              "vs_two_single_passes": round(2 * pms / mms, 2)}
+        del mats, plan, multi, mplan
         torch.cuda.empty_cache()
+
+    # ------------------------------------------ classifier-free-guidance weighted sum (tiny)
+    lat = torch.randn(2, 4 * 128 * 128, device="cuda").to(torch.bfloat16)     # the SDXL latent pair at 1024 x 1024
+    lout = torch.empty_like(lat[0])
+    B.cfg_combine(lat[0], lat[1], 7.5, out=lout)
+    out["cfg_combine"] = {"elements": lat[0].numel(), "us": round(1e3 * float(np.median(time_events(lambda: B.cfg_combine(lat[0], lat[1], 7.5, out=lout), 20))), 2),
+                          "note": "launch-bound: 384 KiB of traffic"}
 
     # ---------------------------------------------------------------- measured ceilings
     # what this device sustains: a register-resident bf16 MFMA loop and a streaming fp32

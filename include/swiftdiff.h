@@ -76,6 +76,21 @@ typedef struct sd_patch_desc {
     float scale;
 } sd_patch_desc;
 
+/* One weight matrix patched with several adapters in one pass (fp32, device pointers). */
+#define SD_PATCH_MAX_ADAPTERS 4
+typedef struct sd_patch_multi_desc {
+    float* W;            /* [out, in], patched in place                                  */
+    float* undo;         /* [out, in] record of W's bits before the patch; required      */
+    uint16_t* serving;   /* [out, in] bf16 copy of the patched W, or NULL                */
+    int32_t out, in;
+    int32_t n_adapters;  /* 1 .. SD_PATCH_MAX_ADAPTERS                                   */
+    int32_t pad_;
+    const float* A[SD_PATCH_MAX_ADAPTERS];   /* A_i [r_i, in]                            */
+    const float* B[SD_PATCH_MAX_ADAPTERS];   /* B_i [out, r_i]                           */
+    int32_t r[SD_PATCH_MAX_ADAPTERS];
+    float scale[SD_PATCH_MAX_ADAPTERS];
+} sd_patch_multi_desc;
+
 const char* sd_last_error(void);
 int32_t sd_version(void);
 
@@ -223,6 +238,28 @@ int sd_patch_plan_build(const sd_patch_desc* descs, int32_t n, void* plan_host, 
                         int64_t* total_tiles);
 int sd_lora_patch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
 int sd_lora_unpatch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
+
+/* ---- lora_patch_multi / lora_unpatch_multi ----------------------------------------------
+ * A request carries one or two LoRAs (Section 3.1, add-on usage table), loaded in parallel
+ * and each merged into the base weights (Section 4.2).  This pass applies up to
+ * SD_PATCH_MAX_ADAPTERS adapters to a matrix while its tile is in registers, in order:
+ *   W_0 = W,  W_i = fl32(W_{i-1} + fl32(scale_i * fl32(B_i A_i))),  W' = W_n,
+ * bit for bit what n successive sd_lora_patch calls give, at the memory traffic of one.
+ * `undo` receives W_0; `serving` (optional) receives bf16(W'), round to nearest even, the
+ * copy the bf16 GEMMs of the forward path read.  unpatch_multi restores W <- undo exactly
+ * and rewrites serving <- bf16(undo).  Plans as for sd_lora_patch (host build, caller uploads). */
+size_t sd_patch_multi_plan_bytes(int32_t n);
+int sd_patch_multi_plan_build(const sd_patch_multi_desc* descs, int32_t n, void* plan_host, size_t plan_bytes,
+                              int64_t* total_tiles);
+int sd_lora_patch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
+int sd_lora_unpatch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream);
+
+/* ---- cfg_combine --------------------------------------------------------------------------
+ * The classifier-free-guidance weighted sum of the two denoised latents of a step
+ * (Section 2, "Diffusion model inference"): out = eps_u + g * (eps_c - eps_u), formed in fp32 as
+ * fl32(eps_u + fl32(g * fl32(eps_c - eps_u))) and rounded to bf16 (nearest even).
+ *   eps_uncond, eps_cond, out   device bf16 [n]; out may alias either input; n elements */
+int sd_cfg_combine(const uint16_t* eps_uncond, const uint16_t* eps_cond, float guidance, uint16_t* out, size_t n, void* stream);
 
 #ifdef __cplusplus
 }

@@ -53,6 +53,16 @@ class sd_patch_desc(C.Structure):
                 ("out", C.c_int32), ("in_", C.c_int32), ("r", C.c_int32), ("scale", C.c_float)]
 
 
+SD_PATCH_MAX_ADAPTERS = 4
+
+
+class sd_patch_multi_desc(C.Structure):
+    _fields_ = [("W", C.c_void_p), ("undo", C.c_void_p), ("serving", C.c_void_p),
+                ("out", C.c_int32), ("in_", C.c_int32), ("n_adapters", C.c_int32), ("pad_", C.c_int32),
+                ("A", C.c_void_p * SD_PATCH_MAX_ADAPTERS), ("B", C.c_void_p * SD_PATCH_MAX_ADAPTERS),
+                ("r", C.c_int32 * SD_PATCH_MAX_ADAPTERS), ("scale", C.c_float * SD_PATCH_MAX_ADAPTERS)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_02031_amd.build` "
@@ -88,6 +98,11 @@ def _load() -> C.CDLL:
         "sd_patch_plan_build": (C.c_int, [P(sd_patch_desc), i32, vp, sz, P(i64)]),
         "sd_lora_patch": (C.c_int, [vp, i32, i64, vp]),
         "sd_lora_unpatch": (C.c_int, [vp, i32, i64, vp]),
+        "sd_patch_multi_plan_bytes": (sz, [i32]),
+        "sd_patch_multi_plan_build": (C.c_int, [P(sd_patch_multi_desc), i32, vp, sz, P(i64)]),
+        "sd_lora_patch_multi": (C.c_int, [vp, i32, i64, vp]),
+        "sd_lora_unpatch_multi": (C.c_int, [vp, i32, i64, vp]),
+        "sd_cfg_combine": (C.c_int, [vp, vp, f32, vp, sz, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -103,7 +118,8 @@ EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
            "sd_multi_lora_linear_workspace_bytes", "sd_multi_lora_linear_fwd", "sd_patch_plan_bytes",
-           "sd_patch_plan_build", "sd_lora_patch", "sd_lora_unpatch"]
+           "sd_patch_plan_build", "sd_lora_patch", "sd_lora_unpatch", "sd_patch_multi_plan_bytes",
+           "sd_patch_multi_plan_build", "sd_lora_patch_multi", "sd_lora_unpatch_multi", "sd_cfg_combine"]
 
 
 def lib() -> C.CDLL:
@@ -302,6 +318,48 @@ class PatchPlan:
         _check(_lib.sd_patch_plan_build(descs, n, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)))
         self.total_tiles = int(tiles.value)
         self.dev = torch.from_numpy(host).cuda()
+
+
+class PatchMultiPlan:
+    """Several adapters per matrix.  Each entry of `mats` is (W, undo, serving_or_None,
+    [(A, B, scale), ...]) with fp32 device tensors W, undo [out, in], A_i [r_i, in],
+    B_i [out, r_i] and an optional bf16 device tensor serving [out, in]."""
+
+    def __init__(self, mats: Sequence[tuple]):
+        n = len(mats)
+        self.n = n
+        self._keep = list(mats)
+        descs = (sd_patch_multi_desc * max(n, 1))()
+        for i, (W, undo, serving, adapters) in enumerate(mats):
+            assert W.dtype == torch.float32 and undo.dtype == torch.float32
+            assert serving is None or serving.dtype == torch.bfloat16
+            d = sd_patch_multi_desc()
+            d.W, d.undo, d.serving = _ptr(W), _ptr(undo), _ptr(serving)
+            d.out, d.in_, d.n_adapters = W.shape[0], W.shape[1], len(adapters)
+            for a, (A, Bm, scale) in enumerate(adapters[:SD_PATCH_MAX_ADAPTERS]):
+                assert A.dtype == torch.float32 and Bm.dtype == torch.float32
+                d.A[a], d.B[a], d.r[a], d.scale[a] = _ptr(A), _ptr(Bm), A.shape[0], float(scale)
+            descs[i] = d
+        nbytes = int(_lib.sd_patch_multi_plan_bytes(n))
+        host = np.zeros(max(nbytes, 64), dtype=np.uint8)
+        tiles = C.c_int64(0)
+        _check(_lib.sd_patch_multi_plan_build(descs, n, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)))
+        self.total_tiles = int(tiles.value)
+        self.dev = torch.from_numpy(host).cuda()
+
+
+def lora_patch_multi(plan: PatchMultiPlan) -> None:
+    _check(_lib.sd_lora_patch_multi(_ptr(plan.dev), plan.n, plan.total_tiles, _stream()))
+
+
+def lora_unpatch_multi(plan: PatchMultiPlan) -> None:
+    _check(_lib.sd_lora_unpatch_multi(_ptr(plan.dev), plan.n, plan.total_tiles, _stream()))
+
+
+def cfg_combine(eps_uncond: torch.Tensor, eps_cond: torch.Tensor, guidance: float, out=None) -> torch.Tensor:
+    y = out if out is not None else torch.empty_like(eps_uncond)
+    _check(_lib.sd_cfg_combine(_ptr(eps_uncond), _ptr(eps_cond), float(guidance), _ptr(y), eps_uncond.numel(), _stream()))
+    return y
 
 
 TIMING_TAGS = {"self_attention": 0, "cross_attention": 1, "qkv": 2, "attn_out": 3, "ff1": 4, "ff2": 5}

@@ -15,7 +15,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswiftdiff.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "patch.hip", "ceilings.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "patch.hip", "ceilings.hip", "guidance.hip"]
 # Per-source extra flags.  The attention kernel does vector arithmetic on MFMA results every
 # tile, so its accumulators must live in ordinary VGPRs (otherwise each use costs an AGPR copy).
 EXTRA = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}

@@ -37,6 +37,14 @@ static_assert(sizeof(PatchPlanEntry) == 64, "plan entry layout");
 
 // workgroup tile: PT_WAVES wavefronts side by side, 32 rows x 128 columns each (two waves
 // per workgroup measured ~4 % faster than four or one on the 310-matrix sweep)
+struct PatchMultiEntry {
+    sd_patch_multi_desc d;
+    int64_t tile_begin;
+    int32_t tiles_c;
+    int32_t ntiles;
+};
+static_assert(sizeof(PatchMultiEntry) % 8 == 0, "plan entry layout");
+
 constexpr int PT_WAVES = 2;
 constexpr int PT_ROWS = 32, PT_COLS = 128 * PT_WAVES;
 constexpr int PT_THREADS = 64 * PT_WAVES;
@@ -48,6 +56,73 @@ __device__ __forceinline__ int find_entry(const PatchPlanEntry* __restrict__ pla
         if (plan[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
     }
     return lo;
+}
+
+// acc[j][v] += sum_k B[row(v)][k] * A[k][col + j] for one adapter on a full tile (all 32 rows
+// and 128 columns inside the matrix, in % 4 == 0): lane l32 supplies B row r0 + l32 and the
+// four A columns col..col+3, k pair (2 kp + hi) per MFMA.
+__device__ __forceinline__ void delta_full(const float* __restrict__ A, const float* __restrict__ B, int r, int in, int r0,
+                                           int col, int l32, int hi, f32x16 (&acc)[4]) {
+    const float* bp = B + (size_t)(r0 + l32) * r + hi;
+    const float* ap = A + (size_t)hi * in + col;
+    const int kp_n = r >> 1;
+    if (r == 32) {
+        // the common rank: every A and B fragment is requested up front (they come out
+        // of L2), so the 64 MFMAs run back to back while the W tile arrives from HBM
+        float bv[16];
+        float4 av[16];
+#pragma unroll
+        for (int kp = 0; kp < 16; ++kp) bv[kp] = bp[2 * kp];
+#pragma unroll
+        for (int kp = 0; kp < 16; ++kp) av[kp] = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+#pragma unroll
+        for (int kp = 0; kp < 16; ++kp) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].y, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].z, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].w, acc[3], 0, 0, 0);
+        }
+    } else {
+#pragma unroll 4
+        for (int kp = 0; kp < kp_n; ++kp) {
+            const float bv = bp[2 * kp];
+            const float4 av = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+        }
+    }
+    if (r & 1) {   // odd rank: last k pairs with a zero
+        const int kk = r - 1;
+        const float bv = hi ? 0.f : B[(size_t)(r0 + l32) * r + kk];
+        float4 av = {0.f, 0.f, 0.f, 0.f};
+        if (!hi) av = *reinterpret_cast<const float4*>(A + (size_t)kk * in + col);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
+    }
+}
+
+// the same product on a ragged tile: every access guarded and scalar
+__device__ __forceinline__ void delta_ragged(const float* __restrict__ A, const float* __restrict__ B, int r, int out, int in,
+                                             int r0, int col, int l32, int hi, f32x16 (&acc)[4]) {
+    const int brow = r0 + l32;
+    const int kp_n = (r + 1) >> 1;
+#pragma unroll 1
+    for (int kp = 0; kp < kp_n; ++kp) {
+        const int kk = 2 * kp + hi;
+        const bool kv = kk < r;
+        const float bv = (kv && brow < out) ? B[(size_t)brow * r + kk] : 0.f;
+        float av[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) av[j] = (kv && col + j < in) ? A[(size_t)kk * in + col + j] : 0.f;
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[0], acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[1], acc[1], 0, 0, 0);
+        acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[2], acc[2], 0, 0, 0);
+        acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[3], acc[3], 0, 0, 0);
+    }
 }
 
 __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_kernel(const PatchPlanEntry* __restrict__ plan, int n) {
@@ -83,46 +158,7 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_kernel(const PatchPl
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             w[v] = NT_LOAD4(W + (size_t)row * in + col);
         }
-        const float* bp = B + (size_t)(r0 + l32) * r + hi;
-        const float* ap = A + (size_t)hi * in + col;
-        const int kp_n = r >> 1;
-        if (r == 32) {
-            // the common rank: every A and B fragment is requested up front (they come out
-            // of L2), so the 64 MFMAs run back to back while the W tile arrives from HBM
-            float bv[16];
-            float4 av[16];
-#pragma unroll
-            for (int kp = 0; kp < 16; ++kp) bv[kp] = bp[2 * kp];
-#pragma unroll
-            for (int kp = 0; kp < 16; ++kp) av[kp] = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
-#pragma unroll
-            for (int kp = 0; kp < 16; ++kp) {
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].x, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].y, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].z, acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].w, acc[3], 0, 0, 0);
-            }
-        } else {
-#pragma unroll 4
-            for (int kp = 0; kp < kp_n; ++kp) {
-                const float bv = bp[2 * kp];
-                const float4 av = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
-                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
-            }
-        }
-        if (r & 1) {   // odd rank: last k pairs with a zero
-            const int kk = r - 1;
-            const float bv = hi ? 0.f : B[(size_t)(r0 + l32) * r + kk];
-            float4 av = {0.f, 0.f, 0.f, 0.f};
-            if (!hi) av = *reinterpret_cast<const float4*>(A + (size_t)kk * in + col);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.x, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.y, acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.z, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av.w, acc[3], 0, 0, 0);
-        }
+        delta_full(A, B, r, in, r0, col, l32, hi, acc);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
@@ -137,21 +173,7 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_kernel(const PatchPl
         }
     } else {
         // ragged tile: same arithmetic, every access guarded and scalar
-        const int brow = r0 + l32;
-        const int kp_n = (r + 1) >> 1;
-#pragma unroll 1
-        for (int kp = 0; kp < kp_n; ++kp) {
-            const int kk = 2 * kp + hi;
-            const bool kv = kk < r;
-            const float bv = (kv && brow < out) ? B[(size_t)brow * r + kk] : 0.f;
-            float av[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) av[j] = (kv && col + j < in) ? A[(size_t)kk * in + col + j] : 0.f;
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[0], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[1], acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[2], acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, av[3], acc[3], 0, 0, 0);
-        }
+        delta_ragged(A, B, r, out, in, r0, col, l32, hi, acc);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
@@ -166,6 +188,147 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_kernel(const PatchPl
             }
         }
     }
+}
+
+__device__ __forceinline__ int find_entry_multi(const PatchMultiEntry* __restrict__ plan, int n, int64_t tile) {
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (plan[mid].tile_begin <= tile) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Several adapters on one matrix in one pass over W (one or two LoRAs per request is the norm,
+// Section 3.1; each is merged as in Section 4.2): the tile's W values stay in registers while
+// the adapters are applied one after the other, W_i = fl32(W_{i-1} + fl32(scale_i * (B_i A_i))),
+// so the result equals successive single patches bit for bit at one third of their traffic for
+// two adapters.  Optionally also writes the bf16 copy of W' that the bf16 GEMMs read.
+__global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const PatchMultiEntry* __restrict__ plan, int n) {
+    const int64_t tile = blockIdx.x;
+    const PatchMultiEntry& E = plan[find_entry_multi(plan, n, tile)];
+    const int out = E.d.out, in = E.d.in, na = E.d.n_adapters;
+    float* __restrict__ W = E.d.W;
+    float* __restrict__ U = E.d.undo;
+    uint16_t* __restrict__ S = E.d.serving;
+    const int local = (int)(tile - E.tile_begin);
+    const int tc = local % E.tiles_c, tr = local / E.tiles_c;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int r0 = tr * PT_ROWS;
+    const int c0 = tc * PT_COLS + wave * 128;
+    if (c0 >= in) return;
+    const int col = c0 + 4 * l32;
+    const bool full = (r0 + 32 <= out) && (c0 + 128 <= in) && ((in & 3) == 0);
+    f32x16 acc[4];
+    if (full) {
+        float4 w[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            w[v] = NT_LOAD4(W + (size_t)row * in + col);
+        }
+#pragma unroll 1
+        for (int a = 0; a < na; ++a) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+            delta_full(E.d.A[a], E.d.B[a], E.d.r[a], in, r0, col, l32, hi, acc);
+            const float scale = E.d.scale[a];
+            if (a == 0) {   // W's old bits go out as soon as they have arrived
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+                    NT_STORE4(U + (size_t)row * in + col, w[v]);
+                }
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                w[v].x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
+                w[v].y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
+                w[v].z = __fadd_rn(w[v].z, __fmul_rn(scale, acc[2][v]));
+                w[v].w = __fadd_rn(w[v].w, __fmul_rn(scale, acc[3][v]));
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            const size_t idx = (size_t)row * in + col;
+            NT_STORE4(W + idx, w[v]);
+            if (S) {
+                bf16x4 o = {(__bf16)w[v].x, (__bf16)w[v].y, (__bf16)w[v].z, (__bf16)w[v].w};
+                *reinterpret_cast<bf16x4*>(S + idx) = o;
+            }
+        }
+    } else {
+        float wv[16][4];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool ok = row < out && col + j < in;
+                wv[v][j] = ok ? W[(size_t)row * in + col + j] : 0.f;
+                if (ok) U[(size_t)row * in + col + j] = wv[v][j];
+            }
+        }
+#pragma unroll 1
+        for (int a = 0; a < na; ++a) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+            delta_ragged(E.d.A[a], E.d.B[a], E.d.r[a], out, in, r0, col, l32, hi, acc);
+            const float scale = E.d.scale[a];
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) wv[v][j] = __fadd_rn(wv[v][j], __fmul_rn(scale, acc[j][v]));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            if (row >= out) continue;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (col + j >= in) continue;
+                const size_t idx = (size_t)row * in + col + j;
+                W[idx] = wv[v][j];
+                if (S) S[idx] = __builtin_bit_cast(uint16_t, (__bf16)wv[v][j]);
+            }
+        }
+    }
+}
+
+// W <- undo (flat linear copy), and the serving copy follows it: bf16(undo)
+__global__ __launch_bounds__(PT_THREADS) void lora_unpatch_multi_kernel(const PatchMultiEntry* __restrict__ plan, int n) {
+    const int64_t tile = blockIdx.x;
+    const PatchMultiEntry& E = plan[find_entry_multi(plan, n, tile)];
+    float* __restrict__ W = E.d.W;
+    const float* __restrict__ U = E.d.undo;
+    uint16_t* __restrict__ S = E.d.serving;
+    const int64_t elems = (int64_t)E.d.out * E.d.in;
+    constexpr int64_t STEP = PT_THREADS * 4;
+    int64_t per = (elems + E.ntiles - 1) / E.ntiles;
+    per = (per + STEP - 1) / STEP * STEP;
+    const int64_t b = (tile - E.tile_begin) * per;
+    const int64_t e = b + per < elems ? b + per : elems;
+    int64_t i = b + threadIdx.x * 4;
+#pragma unroll 4
+    for (; i + 4 <= e; i += STEP) {
+        const float4 v = NT_LOAD4(U + i);
+        NT_STORE4(W + i, v);
+        if (S) {
+            bf16x4 o = {(__bf16)v.x, (__bf16)v.y, (__bf16)v.z, (__bf16)v.w};
+            *reinterpret_cast<bf16x4*>(S + i) = o;
+        }
+    }
+    if (i < e)
+        for (int64_t j = i; j < e; ++j) {
+            W[j] = U[j];
+            if (S) S[j] = __builtin_bit_cast(uint16_t, (__bf16)U[j]);
+        }
 }
 
 // Unpatch: W <- undo, a pure copy.  The matrix's workgroups (as many as the patch pass used)
@@ -244,4 +407,63 @@ extern "C" int sd_lora_patch(const void* plan_dev, int32_t n, int64_t total_tile
 }
 extern "C" int sd_lora_unpatch(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
     return patch_launch(true, plan_dev, n, total_tiles, stream);
+}
+
+extern "C" size_t sd_patch_multi_plan_bytes(int32_t n) { return n > 0 ? (size_t)n * sizeof(PatchMultiEntry) : 0; }
+
+extern "C" int sd_patch_multi_plan_build(const sd_patch_multi_desc* descs, int32_t n, void* plan_host, size_t plan_bytes,
+                                         int64_t* total_tiles) {
+    SD_REQUIRE(n >= 0, SD_EINVAL, "patch plan: n=%d", n);
+    SD_REQUIRE(total_tiles, SD_EINVAL, "patch plan: total_tiles is null");
+    *total_tiles = 0;
+    if (n == 0) return SD_OK;
+    SD_REQUIRE(descs && plan_host, SD_EINVAL, "patch plan: null pointer");
+    SD_REQUIRE(plan_bytes >= sd_patch_multi_plan_bytes(n), SD_EWORKSPACE, "patch plan: buffer of %zu bytes, need %zu", plan_bytes,
+               sd_patch_multi_plan_bytes(n));
+    PatchMultiEntry* plan = static_cast<PatchMultiEntry*>(plan_host);
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        const sd_patch_multi_desc& d = descs[i];
+        SD_REQUIRE(d.W && d.undo && aligned16(d.W) && aligned16(d.undo), SD_EINVAL, "patch desc %d: W and undo must be non-null and 16-byte aligned", i);
+        SD_REQUIRE(d.undo != d.W, SD_EINVAL, "patch desc %d: undo aliases W", i);
+        SD_REQUIRE(!d.serving || (reinterpret_cast<uintptr_t>(d.serving) & 7) == 0, SD_EINVAL, "patch desc %d: serving copy must be 8-byte aligned", i);
+        SD_REQUIRE(d.out > 0 && d.in > 0, SD_EINVAL, "patch desc %d: out=%d in=%d", i, d.out, d.in);
+        SD_REQUIRE(d.n_adapters >= 1 && d.n_adapters <= SD_PATCH_MAX_ADAPTERS, SD_EINVAL, "patch desc %d: %d adapters (1..%d)", i, d.n_adapters,
+                   SD_PATCH_MAX_ADAPTERS);
+        for (int a = 0; a < d.n_adapters; ++a) {
+            SD_REQUIRE(d.A[a] && d.B[a] && aligned16(d.A[a]) && aligned16(d.B[a]), SD_EINVAL,
+                       "patch desc %d adapter %d: A and B must be non-null and 16-byte aligned", i, a);
+            SD_REQUIRE(d.r[a] > 0 && d.r[a] <= 1024, SD_EINVAL, "patch desc %d adapter %d: r=%d", i, a, d.r[a]);
+        }
+        plan[i].d = d;
+        plan[i].tile_begin = total;
+        plan[i].tiles_c = (d.in + PT_COLS - 1) / PT_COLS;
+        const int64_t nt = (int64_t)plan[i].tiles_c * ((d.out + PT_ROWS - 1) / PT_ROWS);
+        SD_REQUIRE(nt < (int64_t)0x7fffffff, SD_EUNSUPPORTED, "patch desc %d: too many tiles", i);
+        plan[i].ntiles = (int32_t)nt;
+        total += nt;
+    }
+    SD_REQUIRE(total < (int64_t)0x7fffffff, SD_EUNSUPPORTED, "patch plan: %lld tiles exceed one grid", (long long)total);
+    *total_tiles = total;
+    return SD_OK;
+}
+
+static int patch_multi_launch(bool undo, const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    SD_REQUIRE(n >= 0 && total_tiles >= 0, SD_EINVAL, "patch: n=%d tiles=%lld", n, (long long)total_tiles);
+    if (n == 0 || total_tiles == 0) return SD_OK;
+    SD_REQUIRE(plan_dev, SD_EINVAL, "patch: plan is null");
+    SD_REQUIRE(total_tiles < (int64_t)0x7fffffff, SD_EUNSUPPORTED, "patch: %lld tiles exceed one grid", (long long)total_tiles);
+    const PatchMultiEntry* plan = static_cast<const PatchMultiEntry*>(plan_dev);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (undo) hipLaunchKernelGGL(lora_unpatch_multi_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), 0, s, plan, n);
+    else hipLaunchKernelGGL(lora_patch_multi_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), 0, s, plan, n);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+
+extern "C" int sd_lora_patch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    return patch_multi_launch(false, plan_dev, n, total_tiles, stream);
+}
+extern "C" int sd_lora_unpatch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, void* stream) {
+    return patch_multi_launch(true, plan_dev, n, total_tiles, stream);
 }

@@ -37,6 +37,7 @@ def test_header_symbols_are_exported(B):
 def test_struct_layouts_match_the_header(B):
     assert C.sizeof(B.sd_proj) == 40
     assert C.sizeof(B.sd_patch_desc) == 48
+    assert C.sizeof(B.sd_patch_multi_desc) == 3 * 8 + 4 * 4 + 4 * 8 + 4 * 8 + 4 * 4 + 4 * 4
     assert C.sizeof(B.sd_block_params) == 6 * 8 + 10 * 40
     assert B.lib().sd_patch_plan_bytes(310) == 310 * 64
 
@@ -74,6 +75,25 @@ def test_patch_plan_build_validates_on_host(B):
         assert L.sd_patch_plan_build(descs, 2, host.ctypes.data_as(C.c_void_p), host.nbytes, C.byref(tiles)) == -1
         assert b"desc 1" in L.sd_last_error()
     assert L.sd_patch_plan_build(None, 0, None, 0, C.byref(tiles)) == 0 and tiles.value == 0
+    # several adapters per matrix
+    md = (B.sd_patch_multi_desc * 1)()
+    md[0].W, md[0].undo, md[0].serving = 0x1000, 0x4000, 0x8008
+    md[0].out, md[0].in_, md[0].n_adapters = 300, 200, 2
+    md[0].A[0], md[0].B[0], md[0].r[0], md[0].scale[0] = 0x2000, 0x3000, 32, 1.0
+    md[0].A[1], md[0].B[1], md[0].r[1], md[0].scale[1] = 0x5000, 0x6000, 7, 0.5
+    mhost = np.zeros(int(L.sd_patch_multi_plan_bytes(1)), np.uint8)
+    assert L.sd_patch_multi_plan_build(md, 1, mhost.ctypes.data_as(C.c_void_p), mhost.nbytes, C.byref(tiles)) == 0 and tiles.value == 10
+    md[0].n_adapters = 5
+    assert L.sd_patch_multi_plan_build(md, 1, mhost.ctypes.data_as(C.c_void_p), mhost.nbytes, C.byref(tiles)) == -1
+    md[0].n_adapters = 2
+    md[0].B[1] = None
+    assert L.sd_patch_multi_plan_build(md, 1, mhost.ctypes.data_as(C.c_void_p), mhost.nbytes, C.byref(tiles)) == -1
+    md[0].B[1] = 0x6000
+    md[0].serving = 0x8004      # not 8-byte aligned
+    assert L.sd_patch_multi_plan_build(md, 1, mhost.ctypes.data_as(C.c_void_p), mhost.nbytes, C.byref(tiles)) == -1
+    # cfg_combine: null pointers with n > 0
+    assert L.sd_cfg_combine(None, None, 7.5, None, 16, None) == -1
+    assert L.sd_cfg_combine(None, None, 7.5, None, 0, None) == 0
 
 
 def test_forward_calls_reject_bad_arguments_before_touching_the_device(B):

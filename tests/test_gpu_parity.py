@@ -331,6 +331,66 @@ def test_patch_exact_integers(B):
     assert np.array_equal(restored[0], W)
 
 
+def test_patch_several_adapters_one_pass(B):
+    """Two and three adapters per matrix in one pass: the oracle's successive-patch chain, the
+    bits of successive single-adapter launches, the bf16 serving copy, and the exact restore."""
+    import torch
+    shapes = ((300, 200), (128, 128), (33, 1027), (640, 640), (64, 256))
+    ranks = ((32, 32), (32, 8, 5), (32,), (16, 32), (32, 32, 32, 32))
+    r = rng(21)
+    host, devm, single = [], [], []
+    for (o, i), rks in zip(shapes, ranks):
+        W = (0.02 * r.standard_normal((o, i))).astype(np.float32)
+        ads = [((0.02 * r.standard_normal((rk, i))).astype(np.float32), (0.02 * r.standard_normal((o, rk))).astype(np.float32), sc)
+               for rk, sc in zip(rks, (1.0, 0.5, 2.0, -1.0))]
+        host.append((W, ads))
+        Wd = torch.from_numpy(W).cuda()
+        devm.append((Wd, torch.empty_like(Wd), torch.empty(Wd.shape, dtype=torch.bfloat16, device="cuda"),
+                     [(torch.from_numpy(A).cuda(), torch.from_numpy(Bm).cuda(), sc) for A, Bm, sc in ads]))
+    plan = B.PatchMultiPlan(devm)
+    B.lora_patch_multi(plan)
+    torch.cuda.synchronize()
+    for (W, ads), (Wd, undo, serving, dads) in zip(host, devm):
+        ref, ref_undo, ref_serving = O.lora_patch_multi(W, ads, serving=True)
+        got = Wd.cpu().numpy()
+        assert rel_err(got, ref) <= PATCH_TOL
+        assert undo.cpu().numpy().tobytes() == W.tobytes()
+        # the serving copy is the rounding of what the GPU itself stored, bit for bit
+        assert serving.float().cpu().numpy().tobytes() == O.bf16_rne(got).tobytes()
+        assert rel_err(serving.float().cpu().numpy(), ref_serving) <= 2.0 ** -7
+        # dropping the last adapter is visible at this tolerance (the check is not vacuous)
+        if len(ads) > 1:
+            assert rel_err(O.lora_patch_multi(W, ads[:-1])[0], ref) > 100 * PATCH_TOL
+        # successive single-adapter launches on a fresh copy give the same bits
+        Ws = torch.from_numpy(W).cuda()
+        for A, Bm, sc in dads:
+            one = B.PatchPlan([(Ws, A, Bm, torch.empty_like(Ws), sc)])
+            B.lora_patch(one)
+        torch.cuda.synchronize()
+        assert Ws.cpu().numpy().tobytes() == got.tobytes()
+    B.lora_unpatch_multi(plan)
+    torch.cuda.synchronize()
+    for (W, ads), (Wd, undo, serving, dads) in zip(host, devm):
+        assert Wd.cpu().numpy().tobytes() == W.tobytes()
+        assert serving.float().cpu().numpy().tobytes() == O.bf16_rne(W).tobytes()
+
+
+def test_cfg_combine_bit_exact(B):
+    import torch
+    r = rng(31)
+    for n, g in ((1, 7.5), (7, 1.0), (4096, 7.5), (2 * 4 * 128 * 128 + 3, 5.0), (65536, 0.0)):
+        eu = G.bf16_round(r.standard_normal(n).astype(np.float32))
+        ec = G.bf16_round(r.standard_normal(n).astype(np.float32))
+        got = B.cfg_combine(dev(eu, B), dev(ec, B), g)
+        assert host(got).tobytes() == O.cfg_combine(eu, ec, g).tobytes()
+    # batch-of-two layout: the two halves of one buffer, unaligned second half, in place
+    n = 1001
+    x = G.bf16_round(r.standard_normal(2 * n).astype(np.float32))
+    xd = dev(x, B)
+    out = B.cfg_combine(xd[:n], xd[n:], 3.0, out=xd[:n])
+    assert host(out).tobytes() == O.cfg_combine(x[:n], x[n:], 3.0).tobytes()
+
+
 # ------------------------------------------------------------------ HIP graph replay
 def test_stack_graph_replay_matches_eager(B):
     """The stack call only enqueues kernels, so it can be captured into a HIP graph.  Every
