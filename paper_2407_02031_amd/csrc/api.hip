@@ -48,6 +48,7 @@ struct ProjOut {
     const void* res; int64_t ldr;
     bool transposed;    // store y^T: y[n * ldy + m]
     int geglu_F;        // > 0: GEGLU epilogue, N == F
+    float alpha;        // output scale applied to the accumulator before bias (0 means 1)
 };
 
 static int check_proj(const sd_proj* p, const char* name, int K) {
@@ -95,7 +96,7 @@ static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
     const int r = p.r;
     GemmProblem G;
     memset(&G, 0, sizeof(G));
-    G.alpha = 1.0f;
+    G.alpha = o.alpha != 0.f ? o.alpha : 1.0f;
     G.bias = p.bias;
     G.res = o.res; G.ldr = o.ldr;
     G.y = o.y; G.ldy = o.ldy; G.y_f32 = o.y_f32;
@@ -178,7 +179,11 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     // sample's keys start at a multiple of 8)
     std::vector<ProjCall> calls;
     calls.push_back({w.n, C, M, C, C, &pq, w.tq, {w.q, C, 0, nullptr, 0, false, 0}});
-    calls.push_back({src, Kkv, Bn * Tk, Kkv, C, &pk, w.tk, {w.k, C, 0, nullptr, 0, false, 0}});
+    // The keys leave their projection multiplied by the softmax scale (in exponent-of-2 units),
+    // applied to the fp32 accumulator before the one rounding to bf16; a k bias would have to
+    // be scaled too, so with one the attention kernel scales the scores itself.
+    const bool k_prescaled = pk.bias == nullptr;
+    calls.push_back({src, Kkv, Bn * Tk, Kkv, C, &pk, w.tk, {w.k, C, 0, nullptr, 0, false, 0, k_prescaled ? ATTN_KSCALE : 0.f}});
     for (int s = 0; s < Bn; ++s)
         calls.push_back({src + (size_t)s * Tk * Kkv, Kkv, Tk, Kkv, C, &pv, w.tv + (size_t)s * Tk * (pv.r > 0 ? pv.r : 0),
                          {w.vt + (size_t)s * Tkp, (int64_t)Bn * Tkp, 0, nullptr, 0, true, 0}});
@@ -186,10 +191,10 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
     int cut = 0;
-    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, w.scratch, w.scratch_bytes, &cut, stream);
+    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, k_prescaled, w.scratch, w.scratch_bytes, &cut, stream);
     timing_mark(atag, 1, stream);
     if (rc) return rc;
-    if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, cut, stream))) return rc;
+    if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, k_prescaled, cut, stream))) return rc;
     ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
     return run_projections(&oc, 1, stream, SD_TIMING_ATTN_OUT);
 }
@@ -336,10 +341,10 @@ extern "C" int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint
     SD_REQUIRE(need == 0 || (ws && w.ok()), SD_EWORKSPACE, "attention: workspace of %zu bytes, need %zu", ws_bytes,
                sd_attention_workspace_bytes(Bn, Tq, Tk, heads));
     int cut = 0;
-    const int rc = launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, scratch, need, &cut,
+    const int rc = launch_attention(q, C, k, C, vt, (int64_t)Bn * Tkp, out, C, Bn, Tq, Tk, Tkp, heads, false, scratch, need, &cut,
                                     static_cast<hipStream_t>(stream));
     if (rc) return rc;
-    return launch_attention_merge(scratch, out, C, Bn, Tq, heads, cut, static_cast<hipStream_t>(stream));
+    return launch_attention_merge(scratch, out, C, Bn, Tq, heads, false, cut, static_cast<hipStream_t>(stream));
 }
 
 extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t Tc, int32_t Dc, int32_t r_max) {

@@ -73,10 +73,15 @@ __device__ __forceinline__ void store_queries(const f32x16 (&o)[2], float l, uin
     }
 }
 
+// PRE: the keys arrive multiplied by 1/8 * log2(e) (the K projection's epilogue does it before
+// rounding to bf16), so a score is already the exponent of 2, and the running reference maximum
+// is subtracted by the matrix core: a fifth k-step multiplies a fragment of ones (K side) with
+// (-m split into three bf16 terms, exact to fp32) on the query side, so the accumulator holds
+// s - m and the vector ALU only exponentiates.  Without PRE one FMA per score does both.
 // nsplit == 0: workgroup i takes tile i.  Otherwise the grid holds nfull whole tiles and
 // 2 * nsplit half tiles (both multiples of 8), dealt so that each XCD, and in dispatch order
 // each CU, first receives its share of whole tiles and then its share of halves.
-template <int QB>
+template <int QB, bool PRE>
 __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __restrict__ q, int64_t ldq,
                                                         const uint16_t* __restrict__ k, int64_t ldk,
                                                         const uint16_t* __restrict__ vt, int64_t ldvt,
@@ -192,7 +197,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
     float m[QB], l[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
-        m[qb] = -INFINITY;
+        m[qb] = PRE ? 0.f : -INFINITY;
         l[qb] = 0.f;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
@@ -213,6 +218,23 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
                 kf[kk][kb] = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, (kk0 + kk) * 2 + hi)]);
             }
     };
+    // PRE: operands of the extra k-step.  K side: 1.0 in k-slots 0..2 of every key row (held by
+    // the lanes of the lower half-wavefront); query side: -m as three bf16 terms in those slots.
+    const u32x4 ones_bits = {hi ? 0u : 0x3F803F80u, hi ? 0u : 0x00003F80u, 0u, 0u};
+    const bf16x8 ones_frag = __builtin_bit_cast(bf16x8, ones_bits);
+    bf16x8 mfrag[QB];
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) mfrag[qb] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    auto set_mfrag = [&](int qb) {
+        const float x = -m[qb];
+        const __bf16 h = (__bf16)x;
+        const float r1 = x - (float)h;
+        const __bf16 md = (__bf16)r1;
+        const __bf16 lo = (__bf16)(r1 - (float)md);
+        const uint32_t w0 = (uint32_t)__builtin_bit_cast(uint16_t, h) | ((uint32_t)__builtin_bit_cast(uint16_t, md) << 16);
+        const uint32_t w1 = (uint32_t)__builtin_bit_cast(uint16_t, lo);
+        mfrag[qb] = __builtin_bit_cast(bf16x8, u32x4{hi ? 0u : w0, hi ? 0u : w1, 0u, 0u});
+    };
     auto compute_s = [&](int t, f32x16 (&s)[QB][2], bf16x8 (&kf0)[2][2]) {
         bf16x8 kf1[2][2];
         load_kfrags(t, 2, kf1);
@@ -222,6 +244,12 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s[qb][kb][v] = 0.f;
+        if (PRE) {
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, mfrag[qb], s[qb][kb], 0, 0, 0);
+        }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -249,7 +277,9 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
     // tile maximum exceeds it by more than RESCALE_LOG2 in the exponent (p <= 2^RESCALE_LOG2
     // stays far inside fp32 / bf16 range), so the O and l rescale runs on the first tiles and
     // almost never afterwards.  This lane's query is column l32, its keys are its registers.
-    auto update_max = [&](f32x16 (&s)[QB][2]) {
+    // PRE: the scores arrive already shifted by m, so the tile maximum is the excess over it; the
+    // segment's first tile always re-references (m starts at 0, not at the scores' level).
+    auto update_max = [&](f32x16 (&s)[QB][2], bool first) {
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
             float mx = fmaxf(s[qb][0][0], s[qb][1][0]);
@@ -260,6 +290,25 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
             float mx_lo, mx_hi;
             both_halves(mx, mx_lo, mx_hi);
             mx = fmaxf(mx_lo, mx_hi);
+            if (PRE) {
+                const bool need = first || mx > RESCALE_LOG2;
+                if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
+                    const float delta = need ? mx : 0.f;
+                    const float alpha = __builtin_amdgcn_exp2f(-delta);
+                    m[qb] += delta;
+                    l[qb] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < 2; ++db)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) o[qb][db][v] *= alpha;
+#pragma unroll
+                    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) s[qb][kb][v] -= delta;
+                    set_mfrag(qb);
+                }
+                continue;
+            }
             const bool need = (mx - m[qb]) * c > RESCALE_LOG2;
             if (__builtin_amdgcn_ballot_w64(need) != 0ull) {
                 const float mnew = need ? mx : m[qb];
@@ -289,8 +338,8 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
                     bf16x8 pk;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p0 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e] * c - mc);
-                        const float p1 = __builtin_amdgcn_exp2f(s[qb][kb][g2 * 8 + 2 * e + 1] * c - mc);
+                        const float p0 = __builtin_amdgcn_exp2f(PRE ? s[qb][kb][g2 * 8 + 2 * e] : s[qb][kb][g2 * 8 + 2 * e] * c - mc);
+                        const float p1 = __builtin_amdgcn_exp2f(PRE ? s[qb][kb][g2 * 8 + 2 * e + 1] : s[qb][kb][g2 * 8 + 2 * e + 1] * c - mc);
                         const bf16x2 pp = {(__bf16)p0, (__bf16)p1};
                         pk[2 * e] = pp[0];
                         pk[2 * e + 1] = pp[1];
@@ -355,7 +404,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
         bf16x8 kf0[2][2];
         load_kfrags(t + 1, 0, kf0);
         __builtin_amdgcn_sched_barrier(0);
-        update_max(cur);
+        update_max(cur, t == s0);
         compute_s(t + 1, nxt, kf0);
         exponentials(cur, pf);
         accumulate_o(vslot, pf);
@@ -371,11 +420,11 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
     if (t + 1 < s1) {            // one more pipelined step, last tile's scores end up in sb
         step(t, sa, sb);
         if (mask_last) mask_tail(nt - 1, sb);
-        update_max(sb);
+        update_max(sb, s1 - s0 == 1);
         exponentials(sb, pf);
     } else {                     // last tile's scores are in sa
         if (mask_last) mask_tail(nt - 1, sa);
-        update_max(sa);
+        update_max(sa, s1 - s0 == 1);
         exponentials(sa, pf);
     }
     // the last tile's V^T landed before the barrier of the step before (or of the prologue)
@@ -452,7 +501,7 @@ size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads) {
 
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
-                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, int* cut_tiles,
+                     int Bn, int Tq, int Tk, int Tkp, int heads, bool k_prescaled, void* scratch, size_t scratch_bytes, int* cut_tiles,
                      hipStream_t stream) {
     SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
     SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
@@ -468,16 +517,22 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     const size_t need = (size_t)nsplit * 2 * PART_FLOATS * sizeof(float);
     if (nsplit > 0 && !(scratch && scratch_bytes >= need && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0)) nsplit = 0;
     const int nfull = (int)tiles - nsplit;
-    hipLaunchKernelGGL(attention_kernel<1>, dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out, ldo,
-                       Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
+    if (k_prescaled)
+        hipLaunchKernelGGL((attention_kernel<1, true>), dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out,
+                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
+    else
+        hipLaunchKernelGGL((attention_kernel<1, false>), dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out,
+                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
     SD_HIP_CHECK(hipGetLastError());
     *cut_tiles = nsplit;
     return SD_OK;
 }
 
-int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, int cut_tiles, hipStream_t stream) {
+int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, bool k_prescaled, int cut_tiles,
+                           hipStream_t stream) {
     if (cut_tiles <= 0) return SD_OK;
-    const float c = 0.125f * 1.44269504088896340736f;
+    // the halves' maxima are in score units, or already in exponent units when the keys were prescaled
+    const float c = k_prescaled ? 1.0f : 0.125f * 1.44269504088896340736f;
     const int qtiles = (Tq + 127) / 128;
     const int nfull = qtiles * heads * Bn - cut_tiles;
     hipLaunchKernelGGL(attention_merge_kernel, dim3((unsigned)cut_tiles), dim3(256), 0, stream, static_cast<const float*>(scratch), out, ldo,

@@ -149,10 +149,13 @@ size_t groupnorm_partials_bytes(int Bn, int T, int groups);
 // some tiles' key range in half (without it every workgroup takes one whole tile)
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
-                     int Bn, int Tq, int Tk, int Tkp, int heads, void* scratch, size_t scratch_bytes, int* cut_tiles,
+                     int Bn, int Tq, int Tk, int Tkp, int heads, bool k_prescaled, void* scratch, size_t scratch_bytes, int* cut_tiles,
                      hipStream_t stream);
 // second kernel of a launch that cut tiles (*cut_tiles > 0 above): merges the halves into `out`
-int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, int cut_tiles, hipStream_t stream);
+int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, bool k_prescaled, int cut_tiles,
+                           hipStream_t stream);
+// softmax scale in exponent-of-2 units: k_prescaled means the keys were multiplied by this
+constexpr float ATTN_KSCALE = 0.125f * 1.44269504088896340736f;
 size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads);
 
 }  // namespace sd
