@@ -133,7 +133,9 @@ def main() -> int:
     flop_per_launch = {
         "self_attention": 4.0 * Bn * T * T * C,
         "cross_attention": 4.0 * Bn * T * cfg.Tc * C,
-        "qkv": 3 * (2.0 * M * C * C + 2.0 * M * r * C),            # base + up-projection (K extended by r)
+        # base + up-projection (K extended by r) of q, k, v, plus the next cross-attention's text
+        # keys / values, which ride in the same grouped launch
+        "qkv": 3 * (2.0 * M * C * C + 2.0 * M * r * C) + 2 * (2.0 * Bn * cfg.Tc * cfg.Dc * C + 2.0 * Bn * cfg.Tc * r * C),
         "attn_out": 2.0 * M * C * C + 2.0 * M * r * C,
         "ff1": 2.0 * M * C * 2 * F + 2.0 * M * rl * 2 * F,
         "ff2": 2.0 * M * F * C + 2.0 * M * rl * C,

@@ -144,9 +144,13 @@ static inline int pad8(int v) { return (v + 7) & ~7; }
 // ---------------------------------------------------------------------------------------
 // sub-layers (shared by the single-call entry points and the stack driver)
 // ---------------------------------------------------------------------------------------
-struct AttnWs { uint16_t *n, *q, *k, *vt, *a, *tq, *tk, *tv, *to; void* scratch; size_t scratch_bytes; };
+struct AttnWs {
+    uint16_t *n, *q, *k, *vt, *a, *tq, *tk, *tv, *to;
+    uint16_t *k2, *vt2, *tk2, *tv2;   // text-context keys / values computed ahead of the cross-attention sub-layer (stack driver)
+    void* scratch; size_t scratch_bytes;
+};
 
-static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, int rmax, int heads) {
+static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, int rmax, int heads, int Tc_ahead = 0) {
     const size_t M = (size_t)Bn * T, Mk = (size_t)Bn * Tk;
     const size_t r = rmax > 0 ? rmax : 8;
     w.n = (uint16_t*)ws.take(M * C * 2);
@@ -158,16 +162,42 @@ static bool carve_attn(Workspace& ws, AttnWs& w, int Bn, int T, int C, int Tk, i
     w.tk = (uint16_t*)ws.take(Mk * r * 2);
     w.tv = (uint16_t*)ws.take(Mk * r * 2);
     w.to = (uint16_t*)ws.take(M * r * 2);
+    const size_t Mc = (size_t)Bn * Tc_ahead;
+    w.k2 = (uint16_t*)ws.take(Mc * C * 2);
+    w.vt2 = (uint16_t*)ws.take((size_t)C * Bn * pad8(Tc_ahead) * 2);
+    w.tk2 = (uint16_t*)ws.take(Mc * r * 2);
+    w.tv2 = (uint16_t*)ws.take(Mc * r * 2);
     // sized for the larger of the two key counts the sub-layer is used with (Tk here, T for self-attention)
     w.scratch_bytes = std::max(attention_scratch_bytes(Bn, T, Tk, heads), attention_scratch_bytes(Bn, T, T, heads));
     w.scratch = ws.take(w.scratch_bytes);
     return ws.ok();
 }
 
+// k and v^T projections of `src` ([Bn * Tk, Kkv]) into kbuf ([Bn * Tk, C]) and vtbuf ([C, Bn * Tkp]:
+// one problem per sample, operands exchanged, so that each sample's keys start at a multiple
+// of 8).  The keys leave their projection multiplied by the softmax scale (in exponent-of-2
+// units), applied to the fp32 accumulator before the one rounding to bf16; a k bias would have
+// to be scaled too, so with one the attention kernel scales the scores itself.
+static bool push_kv_calls(std::vector<ProjCall>& calls, const uint16_t* src, int Kkv, int Tk, const sd_proj& pk, const sd_proj& pv,
+                          uint16_t* kbuf, uint16_t* vtbuf, uint16_t* tkbuf, uint16_t* tvbuf, int Bn, int C) {
+    const int Tkp = pad8(Tk);
+    const bool k_prescaled = pk.bias == nullptr;
+    calls.push_back({src, Kkv, Bn * Tk, Kkv, C, &pk, tkbuf, {kbuf, C, 0, nullptr, 0, false, 0, k_prescaled ? ATTN_KSCALE : 0.f}});
+    for (int s = 0; s < Bn; ++s)
+        calls.push_back({src + (size_t)s * Tk * Kkv, Kkv, Tk, Kkv, C, &pv, tvbuf + (size_t)s * Tk * (pv.r > 0 ? pv.r : 0),
+                         {vtbuf + (size_t)s * Tkp, (int64_t)Bn * Tkp, 0, nullptr, 0, true, 0}});
+    return k_prescaled;
+}
+
+// ahead:    projections that do not depend on x, launched in this sub-layer's grouped GEMMs (the
+//           stack driver puts the next cross-attention's text keys / values here: on their own
+//           their long K loops set the duration of a launch, inside the much larger self-attention
+//           q/k/v launch they are hidden)
+// kv_ready: the context's keys / values are already in w.k2 / w.vt2
 static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx, int Tc, int Dc,
                          const uint16_t* g, const uint16_t* b, float eps, const sd_proj& pq, const sd_proj& pk,
                          const sd_proj& pv, const sd_proj& po, int Bn, int T, int C, int heads, const AttnWs& w,
-                         hipStream_t stream) {
+                         hipStream_t stream, const std::vector<ProjCall>* ahead = nullptr, bool kv_ready = false) {
     const int M = Bn * T;
     const int Tk = ctx ? Tc : T;
     const int Kkv = ctx ? Dc : C;
@@ -175,23 +205,24 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
     if (rc) return rc;
     const uint16_t* src = ctx ? ctx : w.n;
-    // q, k, and v written transposed ([C, Bn * Tkp], one problem per sample so that each
-    // sample's keys start at a multiple of 8)
     std::vector<ProjCall> calls;
+    // first in the group = first in the tile order: the long-K problems start in the first round
+    if (ahead) calls.insert(calls.end(), ahead->begin(), ahead->end());
     calls.push_back({w.n, C, M, C, C, &pq, w.tq, {w.q, C, 0, nullptr, 0, false, 0}});
-    // The keys leave their projection multiplied by the softmax scale (in exponent-of-2 units),
-    // applied to the fp32 accumulator before the one rounding to bf16; a k bias would have to
-    // be scaled too, so with one the attention kernel scales the scores itself.
-    const bool k_prescaled = pk.bias == nullptr;
-    calls.push_back({src, Kkv, Bn * Tk, Kkv, C, &pk, w.tk, {w.k, C, 0, nullptr, 0, false, 0, k_prescaled ? ATTN_KSCALE : 0.f}});
-    for (int s = 0; s < Bn; ++s)
-        calls.push_back({src + (size_t)s * Tk * Kkv, Kkv, Tk, Kkv, C, &pv, w.tv + (size_t)s * Tk * (pv.r > 0 ? pv.r : 0),
-                         {w.vt + (size_t)s * Tkp, (int64_t)Bn * Tkp, 0, nullptr, 0, true, 0}});
+    bool k_prescaled = pk.bias == nullptr;
+    const uint16_t* kbuf = w.k;
+    const uint16_t* vtbuf = w.vt;
+    if (kv_ready) {
+        kbuf = w.k2;
+        vtbuf = w.vt2;
+    } else {
+        k_prescaled = push_kv_calls(calls, src, Kkv, Tk, pk, pv, w.k, w.vt, w.tk, w.tv, Bn, C);
+    }
     if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV))) return rc;
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
     int cut = 0;
-    rc = launch_attention(w.q, C, w.k, C, w.vt, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, k_prescaled, w.scratch, w.scratch_bytes, &cut, stream);
+    rc = launch_attention(w.q, C, kbuf, C, vtbuf, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, k_prescaled, w.scratch, w.scratch_bytes, &cut, stream);
     timing_mark(atag, 1, stream);
     if (rc) return rc;
     if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, k_prescaled, cut, stream))) return rc;
@@ -441,7 +472,7 @@ static bool carve_stack(Workspace& ws, StackWs& w, int Bn, int T, int C, int Tc,
     w.h = (float*)ws.take(M * C * 4);
     w.g = (uint16_t*)ws.take(M * C * 2);
     w.gn = (float*)ws.take(groupnorm_partials_bytes(Bn, T, 32));
-    carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax, C / 64);
+    carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax, C / 64, Tc);
     carve_ff(ws, w.f, (int)M, C, 4 * C, rmax);
     return ws.ok();
 }
@@ -495,8 +526,13 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
     if ((rc = run_projections(&cin, 1, s))) return rc;
     for (int i = 0; i < p->depth; ++i) {
         const sd_block_params& b = p->blocks[i];
-        if ((rc = attn_sublayer(sw.h, sw.h, 1, nullptr, 0, 0, b.ln1_g, b.ln1_b, 1e-5f, b.q1, b.k1, b.v1, b.o1, Bn, T, C, heads, sw.a, s))) return rc;
-        if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s))) return rc;
+        // the text keys / values of this block's cross-attention ride in the self-attention launches
+        std::vector<ProjCall> ahead;
+        push_kv_calls(ahead, ctx, Dc, Tc, b.k2, b.v2, sw.a.k2, sw.a.vt2, sw.a.tk2, sw.a.tv2, Bn, C);
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, nullptr, 0, 0, b.ln1_g, b.ln1_b, 1e-5f, b.q1, b.k1, b.v1, b.o1, Bn, T, C, heads, sw.a, s, &ahead)))
+            return rc;
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s, nullptr, true)))
+            return rc;
         if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s))) return rc;
     }
     // proj_out + input residual, bf16 out
