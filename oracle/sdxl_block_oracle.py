@@ -37,6 +37,10 @@ mathematical properties listed in tests/test_oracle_pins.py, not by paper values
     guidance); the paper cites the guidance formula eps_u + g * (eps_c - eps_u) and
     prints no weights, so g is an argument.
 
+  * Section 4.2, "Bounded asynchronous LoRA loading": adapters load in the background while
+    the base model early-starts unpatched; they are patched at the first step boundary
+    after loading completes, and at step k the base model waits for them.
+
 Parity pins: linear / lora_linear / layernorm / groupnorm / attention / gelu / geglu /
 lora_patch / multi_lora_linear are pinned by brute-force loops, closed forms and
 invariants.  `block` and `spatial_transformer` are compositions with no closed form:
@@ -279,6 +283,28 @@ def cfg_combine(eps_uncond, eps_cond, guidance, out_bf16=True):
     d = (np.float32(guidance) * d).astype(np.float32)
     out = (eu + d).astype(np.float32)
     return bf16_rne(out) if out_bf16 else out
+
+
+def bal_timeline(load_done, step_time, n_steps, k, patch_time=0.0):
+    """Bounded asynchronous LoRA loading as a timeline (Section 4.2): the adapters finish
+    loading `load_done` seconds after the request arrives (the latest of them, since they
+    load in parallel); the base model starts at once, unpatched, one step taking `step_time`.
+    At the boundary before each step (steps count from 1) the loop patches if the adapters
+    are in; at the boundary before step k it waits for them.  Returns (patched_before_step,
+    stall_seconds, total_seconds).  Steps run before the patch are the unpatched ones."""
+    t = 0.0
+    stall = 0.0
+    patched_before = None
+    for step in range(1, n_steps + 1):
+        if patched_before is None:
+            if load_done > t and step >= k:          # the bound: hold the base model
+                stall += load_done - t
+                t = load_done
+            if load_done <= t:
+                patched_before = step
+                t += patch_time
+        t += step_time
+    return patched_before, stall, t
 
 
 def lora_unpatch(W_patched, undo):

@@ -407,6 +407,29 @@ def test_cfg_combine_special_cases():
     assert O.cfg_combine(eu_i, ec_i, 3.0, out_bf16=False).tolist() == [[4.0, 10.0, -9.0]]
 
 
+def test_bal_timeline_closed_forms():
+    d, S, k = 0.1, 50, 20
+    # already loaded: patched before the first step, nothing waits, latency = S steps + the patch
+    assert O.bal_timeline(0.0, d, S, k, patch_time=0.03) == (1, 0.0, pytest.approx(S * d + 0.03))
+    # loaded during step 11 (10 steps done at t = 1.0): the first boundary at or after is before step 12
+    pb, stall, total = O.bal_timeline(1.05, d, S, k)
+    assert (pb, stall) == (12, 0.0) and total == pytest.approx(S * d)
+    # exactly on a boundary counts as loaded
+    assert O.bal_timeline(1.0 + 1e-12, d, S, k)[0] == 12 and O.bal_timeline(1.0 - 1e-9, d, S, k)[0] == 11
+    # slower than the bound: the loop reaches the boundary before step k at (k-1) d and waits
+    pb, stall, total = O.bal_timeline(3.0, d, S, k)
+    assert pb == k and stall == pytest.approx(3.0 - (k - 1) * d) and total == pytest.approx(3.0 + (S - k + 1) * d)
+    # k = 1 is synchronous loading: everything waits, no step runs unpatched
+    pb, stall, total = O.bal_timeline(3.0, d, S, 1)
+    assert (pb, stall) == (1, pytest.approx(3.0)) and total == pytest.approx(3.0 + S * d)
+    # never loaded within the run and no bound inside it: never patched
+    assert O.bal_timeline(1e9, d, S, S + 1)[0] is None
+    # latency saved against load-then-run is min(load, time before the bound)
+    for load in (0.2, 1.0, 1.9, 2.5, 7.0):
+        sync = load + S * d
+        assert sync - O.bal_timeline(load, d, S, k)[2] == pytest.approx(min(load, (k - 1) * d), abs=d)
+
+
 def test_bf16_helpers_roundtrip_and_rne():
     bits = np.arange(0, 0x7F80, 7, dtype=np.uint16)          # positive finite bf16 values
     assert np.array_equal(G.bf16_bits(G.bf16_widen(bits)), bits)
