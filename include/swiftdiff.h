@@ -32,6 +32,8 @@ extern "C" {
 #define SD_EUNSUPPORTED (-2) /* a shape the kernels do not cover (e.g. head dim != 64)      */
 #define SD_EWORKSPACE (-3)   /* workspace missing or too small                              */
 #define SD_EHIP (-4)         /* HIP runtime error; text in sd_last_error()                  */
+#define SD_ETIMEOUT (-5)     /* bal: adapters still loading after the wait at the bound     */
+#define SD_ELOAD (-6)        /* bal: a loader callback reported failure                      */
 
 #define SD_BF16 0
 #define SD_F32 1
@@ -260,6 +262,37 @@ int sd_lora_unpatch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, 
  * fl32(eps_u + fl32(g * fl32(eps_c - eps_u))) and rounded to bf16 (nearest even).
  *   eps_uncond, eps_cond, out   device bf16 [n]; out may alias either input; n elements */
 int sd_cfg_combine(const uint16_t* eps_uncond, const uint16_t* eps_cond, float guidance, uint16_t* out, size_t n, void* stream);
+
+/* ---- bal: bounded asynchronous LoRA loading, host side ------------------------------------
+ * Section 4.2, "Bounded asynchronous LoRA loading (BAL)": when a request arrives its adapters
+ * load in the background, in parallel, while the base model early-starts denoising unpatched;
+ * once they are in, they are patched at the next step boundary; at step k (the bound, found by
+ * profiling where the with/without-LoRA latents start to diverge) the base model is held until
+ * loading completes; after the request the adapters are patched off.  Host logic only: `load`
+ * fills whatever buffers the caller patches from (it runs on a thread of this library, one per
+ * adapter), and the caller issues the copies and sd_lora_patch* calls when told to.
+ *   sd_bal_create(n, load, user)     handle, or NULL (n < 0, or n > 0 without a callback)
+ *   sd_bal_start(b)                  request arrival: starts the n loader threads
+ *   sd_bal_before_step(b, step, k, timeout_s, &patch_now)
+ *        at the boundary before denoising step `step` (from 1).  *patch_now = 1 exactly once,
+ *        at the first boundary where every adapter is loaded: patch, then run the step.  If
+ *        step >= k and loading is not complete, blocks until it is; SD_ETIMEOUT after
+ *        timeout_s seconds, SD_ELOAD if a loader returned non-zero.
+ *   sd_bal_loaded(b)                 1 when every loader has returned
+ *   sd_bal_stats(b, &patched_at_step, &stall_s, &load_s)   any pointer may be NULL; step 0 =
+ *        never patched; load_s < 0 while loading
+ *   sd_bal_finish(b, &unpatch_due)   joins the loaders; *unpatch_due = 1 if a patch was ordered
+ *   sd_bal_destroy(b)
+ * One handle per request; calls on one handle come from one thread. */
+typedef struct sd_bal sd_bal;
+typedef int32_t (*sd_bal_load_fn)(void* user, int32_t adapter);
+sd_bal* sd_bal_create(int32_t n_adapters, sd_bal_load_fn load, void* user);
+int sd_bal_start(sd_bal* b);
+int sd_bal_loaded(sd_bal* b);
+int sd_bal_before_step(sd_bal* b, int32_t step, int32_t k, double timeout_s, int32_t* patch_now);
+int sd_bal_stats(sd_bal* b, int32_t* patched_at_step, double* stall_seconds, double* load_seconds);
+int sd_bal_finish(sd_bal* b, int32_t* unpatch_due);
+void sd_bal_destroy(sd_bal* b);
 
 #ifdef __cplusplus
 }

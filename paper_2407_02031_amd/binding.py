@@ -63,6 +63,9 @@ class sd_patch_multi_desc(C.Structure):
                 ("r", C.c_int32 * SD_PATCH_MAX_ADAPTERS), ("scale", C.c_float * SD_PATCH_MAX_ADAPTERS)]
 
 
+BAL_LOAD_FN = C.CFUNCTYPE(C.c_int32, C.c_void_p, C.c_int32)
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2407_02031_amd.build` "
@@ -103,6 +106,13 @@ def _load() -> C.CDLL:
         "sd_lora_patch_multi": (C.c_int, [vp, i32, i64, vp]),
         "sd_lora_unpatch_multi": (C.c_int, [vp, i32, i64, vp]),
         "sd_cfg_combine": (C.c_int, [vp, vp, f32, vp, sz, vp]),
+        "sd_bal_create": (vp, [i32, BAL_LOAD_FN, vp]),
+        "sd_bal_start": (C.c_int, [vp]),
+        "sd_bal_loaded": (C.c_int, [vp]),
+        "sd_bal_before_step": (C.c_int, [vp, i32, i32, C.c_double, P(i32)]),
+        "sd_bal_stats": (C.c_int, [vp, P(i32), P(C.c_double), P(C.c_double)]),
+        "sd_bal_finish": (C.c_int, [vp, P(i32)]),
+        "sd_bal_destroy": (None, [vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -119,7 +129,8 @@ EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
            "sd_multi_lora_linear_workspace_bytes", "sd_multi_lora_linear_fwd", "sd_patch_plan_bytes",
            "sd_patch_plan_build", "sd_lora_patch", "sd_lora_unpatch", "sd_patch_multi_plan_bytes",
-           "sd_patch_multi_plan_build", "sd_lora_patch_multi", "sd_lora_unpatch_multi", "sd_cfg_combine"]
+           "sd_patch_multi_plan_build", "sd_lora_patch_multi", "sd_lora_unpatch_multi", "sd_cfg_combine", "sd_bal_create", "sd_bal_start",
+           "sd_bal_loaded", "sd_bal_before_step", "sd_bal_stats", "sd_bal_finish", "sd_bal_destroy"]
 
 
 def lib() -> C.CDLL:
@@ -360,6 +371,47 @@ def cfg_combine(eps_uncond: torch.Tensor, eps_cond: torch.Tensor, guidance: floa
     y = out if out is not None else torch.empty_like(eps_uncond)
     _check(_lib.sd_cfg_combine(_ptr(eps_uncond), _ptr(eps_cond), float(guidance), _ptr(y), eps_uncond.numel(), _stream()))
     return y
+
+
+class Bal:
+    """One request's bounded asynchronous adapter loading.  `load(i)` runs on a loader thread of
+    the library (one per adapter) and returns 0 on success; the denoising loop calls
+    `before_step(step, k)` at every step boundary and patches when it returns True."""
+
+    def __init__(self, n_adapters: int, load):
+        self._cb = BAL_LOAD_FN(lambda _user, i: int(load(int(i)) or 0))   # kept alive with the handle
+        self._h = _lib.sd_bal_create(n_adapters, self._cb, None)
+        if not self._h:
+            raise SwiftDiffError(-1, _lib.sd_last_error().decode())
+
+    def start(self) -> None:
+        _check(_lib.sd_bal_start(self._h))
+
+    def loaded(self) -> bool:
+        return bool(_lib.sd_bal_loaded(self._h))
+
+    def before_step(self, step: int, k: int, timeout_s: float = 60.0) -> bool:
+        now = C.c_int32(0)
+        _check(_lib.sd_bal_before_step(self._h, step, k, float(timeout_s), C.byref(now)))
+        return bool(now.value)
+
+    def stats(self):
+        st, stall, load = C.c_int32(0), C.c_double(0.0), C.c_double(0.0)
+        _check(_lib.sd_bal_stats(self._h, C.byref(st), C.byref(stall), C.byref(load)))
+        return {"patched_at_step": st.value, "stall_s": stall.value, "load_s": load.value}
+
+    def finish(self) -> bool:
+        due = C.c_int32(0)
+        _check(_lib.sd_bal_finish(self._h, C.byref(due)))
+        return bool(due.value)
+
+    def close(self) -> None:
+        if self._h:
+            _lib.sd_bal_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
 
 
 TIMING_TAGS = {"self_attention": 0, "cross_attention": 1, "qkv": 2, "attn_out": 3, "ff1": 4, "ff2": 5}

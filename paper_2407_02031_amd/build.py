@@ -15,7 +15,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libswiftdiff.so")
-SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "patch.hip", "ceilings.hip", "guidance.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attention.hip", "norm.hip", "patch.hip", "ceilings.hip", "guidance.hip", "bal.hip"]
 # Per-source extra flags.  The attention kernel does vector arithmetic on MFMA results every
 # tile, so its accumulators must live in ordinary VGPRs (otherwise each use costs an AGPR copy).
 EXTRA = {"attention.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
@@ -50,7 +50,7 @@ def build(verbose: bool = True, jobs: int = 5) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")

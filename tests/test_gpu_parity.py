@@ -3,6 +3,8 @@ by element, at sizes that span several tiles and ragged tails.  Tolerances are t
 task states: max|d|/max|ref| <= 1e-2 for bf16 paths, <= 1e-5 for fp32 patching, unpatch
 bit-exact.  Each call's output is normalised by its own maximum (for residual sub-layers:
 the update, not the residual stream), and negative controls show the check can fail."""
+import time
+
 import numpy as np
 import pytest
 
@@ -389,6 +391,69 @@ def test_cfg_combine_bit_exact(B):
     xd = dev(x, B)
     out = B.cfg_combine(xd[:n], xd[n:], 3.0, out=xd[:n])
     assert host(out).tobytes() == O.cfg_combine(x[:n], x[n:], 3.0).tobytes()
+
+
+def test_bal_orders_the_patch_inside_a_denoising_loop(B):
+    """The serving loop of Section 4.2 in miniature: a projection reads the bf16 serving copy of an
+    fp32 master weight; two adapters load in the background (gated so that they arrive during
+    step 3 of 8); the loop early-starts unpatched, patches when the scheduler says so, and patches
+    off after the request.  Steps before the order equal the base projection, steps after it the
+    patched one, and the master weight ends with its original bits."""
+    import threading
+    import torch
+    r = rng(41)
+    M, K, N, k_bound, n_steps = 192, 256, 320, 6, 8
+    W = (0.05 * r.standard_normal((N, K))).astype(np.float32)
+    ads_h = [((0.3 * r.standard_normal((rk, K))).astype(np.float32), (0.05 * r.standard_normal((N, rk))).astype(np.float32), sc)
+             for rk, sc in ((32, 1.0), (16, 0.5))]
+    x = G.bf16_round(r.standard_normal((M, K)).astype(np.float32))
+    Wd = torch.from_numpy(W).cuda()
+    undo = torch.empty_like(Wd)
+    serving = Wd.to(torch.bfloat16)
+    stage = [(torch.empty(A.shape, dtype=torch.float32).pin_memory(), torch.empty(Bm.shape, dtype=torch.float32).pin_memory()) for A, Bm, _ in ads_h]
+    dev_ads = [(torch.empty(A.shape, dtype=torch.float32, device="cuda"), torch.empty(Bm.shape, dtype=torch.float32, device="cuda"), sc) for A, Bm, sc in ads_h]
+    plan = B.PatchMultiPlan([(Wd, undo, serving, dev_ads)])
+    gate = threading.Event()
+
+    def load(i):                      # loader thread: "disk" -> pinned host memory
+        if not gate.wait(10.0):
+            return 1
+        stage[i][0].copy_(torch.from_numpy(ads_h[i][0]))
+        stage[i][1].copy_(torch.from_numpy(ads_h[i][1]))
+        return 0
+
+    bal = B.Bal(len(ads_h), load)
+    bal.start()
+    xd = dev(x, B)
+    outs, ordered = [], None
+    for step in range(1, n_steps + 1):
+        if step == 4:                 # the adapters arrived during step 3
+            gate.set()
+            t0 = time.time()
+            while not bal.loaded():
+                assert time.time() - t0 < 5.0
+                time.sleep(0.001)
+        if bal.before_step(step, k_bound):
+            ordered = step
+            for (hA, hB), (dA, dB, _) in zip(stage, dev_ads):
+                dA.copy_(hA, non_blocking=True)
+                dB.copy_(hB, non_blocking=True)
+            B.lora_patch_multi(plan)
+        outs.append(host(B.lora_linear_fwd(xd, B.Proj(serving))))
+    assert ordered == 4 and bal.stats()["stall_s"] == 0.0
+    base = O.linear(x, O.bf16_rne(W), None)
+    Wp, _, Wserv = O.lora_patch_multi(W, ads_h, serving=True)
+    patched = O.linear(x, Wserv, None)
+    assert rel_err(patched, base) > 10 * BF16_TOL            # the adapters matter at this tolerance
+    for step, y in enumerate(outs, start=1):
+        assert rel_err(y, base if step < ordered else patched) <= BF16_TOL
+    assert rel_err(Wd.cpu().numpy(), Wp) <= PATCH_TOL
+    assert bal.finish() is True
+    B.lora_unpatch_multi(plan)
+    torch.cuda.synchronize()
+    assert Wd.cpu().numpy().tobytes() == W.tobytes()
+    assert rel_err(host(B.lora_linear_fwd(xd, B.Proj(serving))), base) <= BF16_TOL
+    bal.close()
 
 
 # ------------------------------------------------------------------ HIP graph replay
