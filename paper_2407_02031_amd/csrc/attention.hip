@@ -75,7 +75,7 @@ __device__ __forceinline__ void store_queries(const f32x16 (&o)[2], float l, uin
 
 // PRE: the keys arrive multiplied by 1/8 * log2(e) (the K projection's epilogue does it before
 // rounding to bf16), so a score is already the exponent of 2, and the running reference maximum
-// is subtracted by the matrix core: a fifth k-step multiplies a fragment of ones (K side) with
+// is subtracted by the matrix core: a fifth, half-depth k-step multiplies a fragment of ones (K side) with
 // (-m split into three bf16 terms, exact to fp32) on the query side, so the accumulator holds
 // s - m and the vector ALU only exponentiates.  Without PRE one FMA per score does both.
 // nsplit == 0: workgroup i takes tile i.  Otherwise the grid holds nfull whole tiles and
@@ -218,13 +218,14 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
                 kf[kk][kb] = __builtin_bit_cast(bf16x8, lk[r * 8 + aswz(r, (kk0 + kk) * 2 + hi)]);
             }
     };
-    // PRE: operands of the extra k-step.  K side: 1.0 in k-slots 0..2 of every key row (held by
-    // the lanes of the lower half-wavefront); query side: -m as three bf16 terms in those slots.
-    const u32x4 ones_bits = {hi ? 0u : 0x3F803F80u, hi ? 0u : 0x00003F80u, 0u, 0u};
-    const bf16x8 ones_frag = __builtin_bit_cast(bf16x8, ones_bits);
-    bf16x8 mfrag[QB];
+    // PRE: operands of the extra k-step, a 32x32x8 MFMA (half the cost of a 16-deep one; a lane
+    // supplies k-slots 4*hi .. 4*hi+3).  K side: 1.0 in k-slots 0..2 of every key row; query side:
+    // -m as three bf16 terms in those slots; the upper half-wavefront supplies zeros.
+    const u32x2 ones_bits = {hi ? 0u : 0x3F803F80u, hi ? 0u : 0x00003F80u};
+    const bf16x4 ones_frag = __builtin_bit_cast(bf16x4, ones_bits);
+    bf16x4 mfrag[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) mfrag[qb] = __builtin_bit_cast(bf16x8, u32x4{0u, 0u, 0u, 0u});
+    for (int qb = 0; qb < QB; ++qb) mfrag[qb] = __builtin_bit_cast(bf16x4, u32x2{0u, 0u});
     auto set_mfrag = [&](int qb) {
         const float x = -m[qb];
         const __bf16 h = (__bf16)x;
@@ -233,7 +234,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
         const __bf16 lo = (__bf16)(r1 - (float)md);
         const uint32_t w0 = (uint32_t)__builtin_bit_cast(uint16_t, h) | ((uint32_t)__builtin_bit_cast(uint16_t, md) << 16);
         const uint32_t w1 = (uint32_t)__builtin_bit_cast(uint16_t, lo);
-        mfrag[qb] = __builtin_bit_cast(bf16x8, u32x4{hi ? 0u : w0, hi ? 0u : w1, 0u, 0u});
+        mfrag[qb] = __builtin_bit_cast(bf16x4, u32x2{hi ? 0u : w0, hi ? 0u : w1});
     };
     auto compute_s = [&](int t, f32x16 (&s)[QB][2], bf16x8 (&kf0)[2][2]) {
         bf16x8 kf1[2][2];
@@ -248,7 +249,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_frag, mfrag[qb], s[qb][kb], 0, 0, 0);
+                for (int kb = 0; kb < 2; ++kb) s[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ones_frag, mfrag[qb], s[qb][kb], 0, 0, 0);
         }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
