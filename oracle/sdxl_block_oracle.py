@@ -147,6 +147,18 @@ def groupnorm(x, gamma, beta, groups=GN_GROUPS, eps=GN_EPS, dtype=np.float64):
     return y * _as(gamma, dtype) + _as(beta, dtype)
 
 
+def silu(z):
+    """z * sigmoid(z)."""
+    z = np.asarray(z)
+    return z / (1.0 + np.exp(-z))
+
+
+def groupnorm_silu(x, gamma, beta, groups=GN_GROUPS, eps=GN_EPS, dtype=np.float64):
+    """GroupNorm followed by SiLU, the pair the base model's ResNet blocks apply and the
+    paper fuses into one operator (Section 4.3, "Kernel-level optimizations")."""
+    return silu(groupnorm(x, gamma, beta, groups, eps, dtype))
+
+
 # --------------------------------------------------------------------------- #
 # attention
 # --------------------------------------------------------------------------- #

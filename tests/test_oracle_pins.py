@@ -407,6 +407,23 @@ def test_cfg_combine_special_cases():
     assert O.cfg_combine(eu_i, ec_i, 3.0, out_bf16=False).tolist() == [[4.0, 10.0, -9.0]]
 
 
+def test_silu_closed_forms_and_groupnorm_silu_composition():
+    assert O.silu(np.array([0.0]))[0] == 0.0
+    z = np.array([-30.0, -2.0, -0.5, 0.5, 2.0, 30.0])
+    want = [v / (1.0 + math.exp(-v)) for v in z]
+    assert np.allclose(O.silu(z), want, rtol=1e-14, atol=0)
+    assert np.allclose(O.silu(z) - O.silu(-z), z, rtol=1e-13)          # silu(z) - silu(-z) = z
+    assert abs(O.silu(np.array([30.0]))[0] - 30.0) < 1e-11 and abs(O.silu(np.array([-30.0]))[0]) < 1e-11
+    assert O.silu(np.array([-1.278]))[0] == pytest.approx(-0.27846, abs=1e-5)   # the minimum of z*sigmoid(z)
+    r = np.random.default_rng(3)
+    x = r.standard_normal((2, 9, 64)); g = 1 + 0.1 * r.standard_normal(64); b = 0.1 * r.standard_normal(64)
+    y = O.groupnorm_silu(x, g, b)
+    n = O.groupnorm(x, g, b)
+    for idx in ((0, 0, 0), (1, 8, 63), (0, 4, 31)):
+        assert y[idx] == pytest.approx(n[idx] / (1.0 + math.exp(-n[idx])), rel=1e-13)
+    assert rel_err(O.groupnorm(x, g, b), y) > 0.1                        # the activation is not a no-op
+
+
 def test_bal_timeline_closed_forms():
     d, S, k = 0.1, 50, 20
     # already loaded: patched before the first step, nothing waits, latency = S steps + the patch
