@@ -191,6 +191,12 @@ size_t sd_groupnorm_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t gr
 int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
                      int32_t Bn, int32_t T, int32_t C, int32_t groups, float eps,
                      void* ws, size_t ws_bytes, void* stream);
+/* The same followed by SiLU, y = n * sigmoid(n): the GroupNorm + SiLU pair of the base model's
+ * ResNet blocks as one operator (Section 4.3, "Kernel-level optimizations").  Same arguments
+ * and workspace. */
+int sd_groupnorm_silu_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
+                          int32_t Bn, int32_t T, int32_t C, int32_t groups, float eps,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /* ---- spatial_transformer_fwd ----------------------------------------------------------
  * The whole hot path on the guidance pair (Section 3.3: both latents in one batch):

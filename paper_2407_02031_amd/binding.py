@@ -92,6 +92,7 @@ def _load() -> C.CDLL:
         "sd_ff_block_fwd": (C.c_int, [vp, vp, i32, vp, vp, f32, P(sd_proj), P(sd_proj), i32, i32, i32, vp, sz, vp]),
         "sd_groupnorm_workspace_bytes": (sz, [i32, i32, i32, i32]),
         "sd_groupnorm_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]),
+        "sd_groupnorm_silu_fwd": (C.c_int, [vp, vp, vp, vp, i32, i32, i32, i32, f32, vp, sz, vp]),
         "sd_spatial_transformer_workspace_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "sd_spatial_transformer_fwd": (C.c_int, [vp, vp, P(sd_stack_params), vp, i32, i32, i32, i32, i32, i32, vp, sz, vp]),
         "sd_multi_lora_linear_workspace_bytes": (sz, [i32, i32]),
@@ -125,7 +126,7 @@ _lib = _load()
 EXPORTS = ["sd_last_error", "sd_version", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32",
            "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_workspace_bytes", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
-           "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd",
+           "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd", "sd_groupnorm_silu_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
            "sd_multi_lora_linear_workspace_bytes", "sd_multi_lora_linear_fwd", "sd_patch_plan_bytes",
            "sd_patch_plan_build", "sd_lora_patch", "sd_lora_unpatch", "sd_patch_multi_plan_bytes",
@@ -271,6 +272,14 @@ def groupnorm_fwd(x: torch.Tensor, gamma, beta, groups: int = 32, eps: float = 1
     y = out if out is not None else torch.empty_like(x)
     w = _ws(_lib.sd_groupnorm_workspace_bytes(Bn, T, Cc, groups), ws)
     _check(_lib.sd_groupnorm_fwd(_ptr(x), _ptr(y), _ptr(gamma), _ptr(beta), Bn, T, Cc, groups, eps, _ptr(w), w.numel(), _stream()))
+    return y
+
+
+def groupnorm_silu_fwd(x: torch.Tensor, gamma, beta, groups: int = 32, eps: float = 1e-6, out=None, ws=None) -> torch.Tensor:
+    Bn, T, Cc = x.shape
+    y = out if out is not None else torch.empty_like(x)
+    w = _ws(_lib.sd_groupnorm_workspace_bytes(Bn, T, Cc, groups), ws)
+    _check(_lib.sd_groupnorm_silu_fwd(_ptr(x), _ptr(y), _ptr(gamma), _ptr(beta), Bn, T, Cc, groups, eps, _ptr(w), w.numel(), _stream()))
     return y
 
 

@@ -451,7 +451,7 @@ extern "C" size_t sd_groupnorm_workspace_bytes(int32_t Bn, int32_t T, int32_t C,
     return round_up(groupnorm_partials_bytes(Bn, T, groups), 256);
 }
 
-extern "C" int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta, int32_t Bn,
+static int groupnorm_entry(bool silu, const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta, int32_t Bn,
                                 int32_t T, int32_t C, int32_t groups, float eps, void* ws, size_t ws_bytes, void* stream) {
     SD_REQUIRE(Bn >= 0 && T >= 0 && C > 0 && groups > 0, SD_EINVAL, "groupnorm: Bn=%d T=%d C=%d groups=%d", Bn, T, C, groups);
     if (Bn == 0 || T == 0) return SD_OK;
@@ -459,7 +459,17 @@ extern "C" int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* 
     SD_REQUIRE(aligned16(x) && aligned16(y) && aligned16(gamma) && aligned16(beta), SD_EINVAL, "groupnorm: misaligned pointer");
     SD_REQUIRE(ws && ws_bytes >= sd_groupnorm_workspace_bytes(Bn, T, C, groups), SD_EWORKSPACE, "groupnorm: workspace of %zu bytes, need %zu",
                ws_bytes, sd_groupnorm_workspace_bytes(Bn, T, C, groups));
-    return launch_groupnorm(x, y, gamma, beta, Bn, T, C, groups, eps, static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+    return launch_groupnorm(x, y, gamma, beta, Bn, T, C, groups, eps, static_cast<float*>(ws), static_cast<hipStream_t>(stream), silu);
+}
+
+extern "C" int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta, int32_t Bn,
+                                int32_t T, int32_t C, int32_t groups, float eps, void* ws, size_t ws_bytes, void* stream) {
+    return groupnorm_entry(false, x, y, gamma, beta, Bn, T, C, groups, eps, ws, ws_bytes, stream);
+}
+
+extern "C" int sd_groupnorm_silu_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta, int32_t Bn,
+                                     int32_t T, int32_t C, int32_t groups, float eps, void* ws, size_t ws_bytes, void* stream) {
+    return groupnorm_entry(true, x, y, gamma, beta, Bn, T, C, groups, eps, ws, ws_bytes, stream);
 }
 
 // ---------------------------------------------------------------------------------------

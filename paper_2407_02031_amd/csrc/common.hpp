@@ -142,7 +142,7 @@ int launch_cvt_bf16_to_f32(const uint16_t* x, float* y, size_t n, hipStream_t st
 int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t stream);
 
 int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
-                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream);
+                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream, bool silu = false);
 size_t groupnorm_partials_bytes(int Bn, int T, int groups);
 
 // scratch: attention_scratch_bytes(...) bytes, 16-byte aligned, for the launches that cut

@@ -208,6 +208,9 @@ __global__ __launch_bounds__(64) void groupnorm_finalize_kernel(const uint16_t* 
     }
 }
 
+// SILU: y = n * sigmoid(n) on the normalised value, the GroupNorm + SiLU pair of the base model's
+// ResNet blocks as one operator (Section 4.3, "Kernel-level optimizations")
+template <bool SILU>
 __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                        const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ beta,
                                        const float* __restrict__ stats, int T, int C, int groups) {
@@ -229,8 +232,12 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
 #pragma unroll 8
     for (int t = t0; t < t1; ++t) {
         const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
-        const float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
-        const float o1 = (bf16hi_to_f32(pr) - mean) * g1 + b1;
+        float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
+        float o1 = (bf16hi_to_f32(pr) - mean) * g1 + b1;
+        if (SILU) {
+            o0 = o0 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * o0));
+            o1 = o1 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * o1));
+        }
         reinterpret_cast<uint32_t*>(yb + (size_t)t * C)[cp] = pack_bf16x2(o0, o1);
     }
 }
@@ -241,7 +248,7 @@ size_t groupnorm_partials_bytes(int Bn, int T, int groups) {
 }
 
 int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
-                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream) {
+                     int Bn, int T, int C, int groups, float eps, float* partials, hipStream_t stream, bool silu) {
     SD_REQUIRE(groups > 0 && C % groups == 0 && (C / groups) % 2 == 0, SD_EUNSUPPORTED,
                "groupnorm: C=%d groups=%d (need an even number of channels per group)", C, groups);
     SD_REQUIRE(C <= 2048, SD_EUNSUPPORTED, "groupnorm: C=%d > 2048", C);
@@ -256,7 +263,8 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
     float* stats = partials + round_up((size_t)Bn * nchunks * groups * 2 * sizeof(float), 256) / sizeof(float);
     hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(Bn * groups), dim3(64), 0, stream, x, partials, stats, T, C, groups, nchunks, eps);
     SD_HIP_CHECK(hipGetLastError());
-    hipLaunchKernelGGL(groupnorm_apply_kernel, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
+    if (silu) hipLaunchKernelGGL(groupnorm_apply_kernel<true>, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
+    else hipLaunchKernelGGL(groupnorm_apply_kernel<false>, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }

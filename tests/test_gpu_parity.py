@@ -242,6 +242,11 @@ def test_groupnorm_matches_oracle(B, Bn, T, C):
     ref = O.groupnorm(x, g, b)
     y = B.groupnorm_fwd(dev(x, B), dev(g, B), dev(b, B))
     assert rel_err(host(y), ref) <= BF16_TOL
+    # the fused GroupNorm + SiLU operator of the ResNet blocks
+    ref_s = O.groupnorm_silu(x, g, b)
+    ys = B.groupnorm_silu_fwd(dev(x, B), dev(g, B), dev(b, B))
+    assert rel_err(host(ys), ref_s) <= BF16_TOL
+    assert rel_err(ref, ref_s) > 10 * BF16_TOL          # the activation is visible at this tolerance
 
 
 # ------------------------------------------------------------ spatial_transformer_fwd
