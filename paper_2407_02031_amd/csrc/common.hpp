@@ -128,6 +128,7 @@ constexpr int GEMM_MAX_PROBLEMS = 16;
 struct GemmGroup {
     int32_t n;
     int32_t total_tiles;
+    int32_t first_tile[GEMM_MAX_PROBLEMS];   // copy of p[i].tile_begin, read by every workgroup in one scalar load
     GemmProblem p[GEMM_MAX_PROBLEMS];
 };
 

@@ -109,11 +109,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
         const int total = gridDim.x;
         if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
     }
+    // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
+    // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
+    // problem pay a second round.
     int pi = 0;
-#pragma unroll 1
-    for (int i = 1; i < g.n; ++i)
-        if (tile >= g.p[i].tile_begin) pi = i;
-    const GemmProblem& P = g.p[pi];
+#pragma unroll
+    for (int i = 1; i < GEMM_MAX_PROBLEMS; ++i)
+        if (i < g.n && tile >= g.first_tile[i]) pi = i;
+    GemmProblem P = g.p[0];
+    if (pi != 0) P = g.p[pi];
     const int local = tile - P.tile_begin;
     const int band_tiles = 8 * P.tiles_n;
     const int band = local / band_tiles, rem = local - band * band_tiles;
@@ -418,6 +422,7 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
         P.tiles_m = (P.Mp + BM - 1) / BM;
         P.tiles_n = (P.N + BN_OUT - 1) / BN_OUT;
         P.tile_begin = total;
+        g.first_tile[i] = total;
         total += P.tiles_m * P.tiles_n;
     }
     g.total_tiles = total;
