@@ -95,6 +95,12 @@ typedef struct sd_patch_multi_desc {
 
 const char* sd_last_error(void);
 int32_t sd_version(void);
+/* Self-check of the projection launches (Section 2's LoRA projection as one launch: tiles of
+ * the base GEMM wait, behind a bounded spin, for the down-projection tiles of the same launch):
+ * *count receives how many tiles, since the library was loaded, ran out of spins.  Always 0
+ * unless that protocol is broken, in which case outputs were wrong.  count: host.
+ * Synchronises the device. */
+int sd_gemm_dep_timeouts(int64_t* count);
 
 /* ---- instrumentation (off by default) --------------------------------------------------
  * Measurement support for the roofline figures: when enabled, the sub-layer and stack calls

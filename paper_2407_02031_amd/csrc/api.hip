@@ -80,17 +80,18 @@ struct ProjCall {
     const sd_proj* p; uint16_t* tbuf; ProjOut o;
 };
 
-static int push_down(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
+static int push_down(GemmGroup& g, hipStream_t stream, const ProjCall& c, int32_t* signal = nullptr) {
     const sd_proj& p = *c.p;
     if (p.r <= 0) return SD_OK;
     GemmProblem D;
     memset(&D, 0, sizeof(D));
     D.p0 = c.x; D.ldp0 = c.ldx; D.q0 = p.A; D.ldq0 = c.K;
     D.y = c.tbuf; D.ldy = p.r; D.Mp = c.M; D.N = p.r; D.K0 = c.K; D.K1 = 0; D.alpha = p.scale;
+    D.signal = signal;
     return push(g, D, stream);
 }
 
-static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
+static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c, const int32_t* wait = nullptr) {
     const sd_proj& p = *c.p;
     const ProjOut& o = c.o;
     const int r = p.r;
@@ -112,22 +113,77 @@ static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c) {
         G.Mp = c.N; G.N = c.M;
         G.bias_on_rows = 1;
     }
+    if (r) { G.wait = wait; G.wait_cols = o.transposed; }
     return push(g, G, stream);
 }
 
 static int flush(GemmGroup& g, hipStream_t stream) {
     if (g.n == 0) return SD_OK;
     int rc = launch_gemm_group(g, stream);
-    g.n = 0;
+    memset(&g, 0, sizeof(g));
     return rc;
 }
 
-// Run independent projections: every down-projection first (grouped launches), then every
-// base GEMM (grouped launches), so no base GEMM can read a down-projection still in flight.
-static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1) {
+// Flags for launches whose base GEMMs wait, tile by tile, for down-projections of the same
+// launch: two arrays of `cap` flags in the caller's workspace.  A launch signals in one array
+// and clears the other for the next launch; the first launch of a call follows clear().
+struct DepFlags {
+    int32_t* f[2] = {nullptr, nullptr};
+    int cap = 0;
+    int turn = 0;
+    static int cap_for(size_t rows) { return (int)(4 * ((rows + 63) / 64) + 64); }
+    static size_t bytes_for(size_t rows) { return round_up((size_t)cap_for(rows) * 4, 256) * 2; }
+    bool carve(Workspace& ws, size_t rows) {
+        cap = cap_for(rows);
+        char* b = (char*)ws.take(bytes_for(rows));
+        f[0] = (int32_t*)b;
+        f[1] = b ? (int32_t*)(b + bytes_for(rows) / 2) : nullptr;
+        turn = 0;
+        return b != nullptr;
+    }
+    int clear(hipStream_t stream) { turn = 0; return launch_clear_flags(f[0], cap, stream); }
+};
+
+// Run independent projections.  With flags, as one launch: down-projection tiles first, and a
+// base GEMM tile waits for the down-projection rows it reads just before its second K segment
+// (by then they are long done, except in the first round of workgroups).  Without, or when the
+// projections do not fit one group or include a GEGLU, as two rounds of launches: every
+// down-projection, then every base GEMM.
+static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1, DepFlags* dep = nullptr) {
     GemmGroup g;
-    g.n = 0;
+    memset(&g, 0, sizeof(g));
     int rc;
+    if (dep && dep->f[0]) {
+        int problems = 0, downs = 0;
+        size_t flags = 0;
+        bool geglu = false;
+        for (int i = 0; i < n; ++i) {
+            if (calls[i].M <= 0) continue;
+            ++problems;
+            if (calls[i].o.geglu_F > 0) geglu = true;
+            if (calls[i].p->r > 0) { ++problems; ++downs; flags += ((size_t)calls[i].M + 63) / 64; }
+        }
+        if (downs > 0 && problems <= GEMM_MAX_PROBLEMS && flags <= (size_t)dep->cap && !geglu) {
+            int32_t* const base = dep->f[dep->turn];
+            std::vector<int32_t*> slot(n, nullptr);
+            size_t used = 0;
+            for (int i = 0; i < n; ++i) {
+                if (calls[i].M <= 0 || calls[i].p->r <= 0) continue;
+                slot[i] = base + used;
+                used += ((size_t)calls[i].M + 63) / 64;
+                if ((rc = push_down(g, stream, calls[i], slot[i]))) return rc;
+            }
+            for (int i = 0; i < n; ++i)
+                if (calls[i].M > 0 && (rc = push_main(g, stream, calls[i], slot[i]))) return rc;
+            dep->turn ^= 1;
+            g.zero_ptr = dep->f[dep->turn];
+            g.zero_n = dep->cap;
+            timing_mark(tag, 0, stream);
+            rc = flush(g, stream);
+            timing_mark(tag, 1, stream);
+            return rc;
+        }
+    }
     for (int i = 0; i < n; ++i)
         if (calls[i].M > 0 && (rc = push_down(g, stream, calls[i]))) return rc;
     if ((rc = flush(g, stream))) return rc;
@@ -197,7 +253,7 @@ static bool push_kv_calls(std::vector<ProjCall>& calls, const uint16_t* src, int
 static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx, int Tc, int Dc,
                          const uint16_t* g, const uint16_t* b, float eps, const sd_proj& pq, const sd_proj& pk,
                          const sd_proj& pv, const sd_proj& po, int Bn, int T, int C, int heads, const AttnWs& w,
-                         hipStream_t stream, const std::vector<ProjCall>* ahead = nullptr, bool kv_ready = false) {
+                         hipStream_t stream, const std::vector<ProjCall>* ahead = nullptr, bool kv_ready = false, DepFlags* dep = nullptr) {
     const int M = Bn * T;
     const int Tk = ctx ? Tc : T;
     const int Kkv = ctx ? Dc : C;
@@ -218,7 +274,7 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     } else {
         k_prescaled = push_kv_calls(calls, src, Kkv, Tk, pk, pv, w.k, w.vt, w.tk, w.tv, Bn, C);
     }
-    if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV))) return rc;
+    if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV, dep))) return rc;
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
     int cut = 0;
@@ -227,7 +283,7 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     if (rc) return rc;
     if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, k_prescaled, cut, stream))) return rc;
     ProjCall oc = {w.a, C, M, C, C, &po, w.to, {y, C, io_f32, x, C, false, 0}};
-    return run_projections(&oc, 1, stream, SD_TIMING_ATTN_OUT);
+    return run_projections(&oc, 1, stream, SD_TIMING_ATTN_OUT, dep);
 }
 
 struct FfWs { uint16_t *n, *g, *t1, *t2; };
@@ -242,13 +298,13 @@ static bool carve_ff(Workspace& ws, FfWs& w, int M, int C, int F, int rmax) {
 }
 
 static int ff_sublayer(const void* x, void* y, int io_f32, const uint16_t* g, const uint16_t* b, float eps,
-                       const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream) {
+                       const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream, DepFlags* dep = nullptr) {
     int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
     if (rc) return rc;
     ProjCall c1 = {w.n, C, M, C, F, &p1, w.t1, {w.g, F, 0, nullptr, 0, false, F}};
-    if ((rc = run_projections(&c1, 1, stream, SD_TIMING_FF1))) return rc;
+    if ((rc = run_projections(&c1, 1, stream, SD_TIMING_FF1, dep))) return rc;
     ProjCall c2 = {w.g, F, M, F, C, &p2, w.t2, {y, C, io_f32, x, C, false, 0}};
-    return run_projections(&c2, 1, stream, SD_TIMING_FF2);
+    return run_projections(&c2, 1, stream, SD_TIMING_FF2, dep);
 }
 
 static int rmax_of(const sd_proj* const* ps, int n) {
@@ -264,6 +320,13 @@ using namespace sd;
 
 extern "C" const char* sd_last_error(void) { return g_err; }
 extern "C" int32_t sd_version(void) { return 1; }
+extern "C" int sd_gemm_dep_timeouts(int64_t* count) {
+    SD_REQUIRE(count, SD_EINVAL, "gemm_dep_timeouts: null count");
+    long long v = 0;
+    int rc = gemm_dep_timeouts(&v);
+    *count = v;
+    return rc;
+}
 
 extern "C" int sd_timing_enable(int32_t records_per_tag) {
     SD_REQUIRE(records_per_tag > 0 && records_per_tag <= 65536, SD_EINVAL, "timing: records_per_tag=%d", records_per_tag);
@@ -314,6 +377,7 @@ extern "C" size_t sd_lora_linear_workspace_bytes(int32_t M, int32_t N, int32_t K
     size_t total = 0;
     if (has_ln) total += round_up((size_t)M * K * 2, 256);
     total += round_up((size_t)M * (r > 0 ? r : 8) * 2, 256);
+    if (r > 0) total += DepFlags::bytes_for(M);
     (void)ws;
     return total;
 }
@@ -346,9 +410,12 @@ extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj*
         xin = n;
     }
     uint16_t* t = (uint16_t*)w.take((size_t)M * (p->r > 0 ? p->r : 8) * 2);
+    DepFlags dep;
+    if (p->r > 0) dep.carve(w, M);
     SD_REQUIRE(w.ok(), SD_EWORKSPACE, "lora_linear: workspace too small");
+    if (p->r > 0 && epilogue != SD_EPI_GEGLU && (rc = dep.clear(s))) return rc;
     ProjCall c = {xin, K, M, K, N, p, t, {y, N, y_dtype == SD_F32, residual, N, false, epilogue == SD_EPI_GEGLU ? N : 0}};
-    return run_projections(&c, 1, s);
+    return run_projections(&c, 1, s, -1, &dep);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -384,7 +451,7 @@ extern "C" size_t sd_attn_block_workspace_bytes(int32_t Bn, int32_t T, int32_t C
     Workspace ws((void*)256, (size_t)-1 / 2);
     AttnWs w;
     carve_attn(ws, w, Bn, T, C, Tc > 0 ? (Tc > T ? Tc : T) : T, r_max, C / 64);
-    return ws.used;
+    return ws.used + DepFlags::bytes_for((size_t)Bn * (Tc > T ? Tc : T));
 }
 
 extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const uint16_t* ctx, int32_t Tc, int32_t Dc,
@@ -409,9 +476,12 @@ extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const
     const int Tk = ctx ? Tc : T;
     Workspace w(ws, ws_bytes);
     AttnWs aw;
-    SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax, heads), SD_EWORKSPACE, "attn_block: workspace of %zu bytes is too small", ws_bytes);
+    DepFlags dep;
+    SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax, heads) && dep.carve(w, (size_t)Bn * (Tk > T ? Tk : T)), SD_EWORKSPACE,
+               "attn_block: workspace of %zu bytes is too small", ws_bytes);
+    if ((rc = dep.clear(static_cast<hipStream_t>(stream)))) return rc;
     return attn_sublayer(x, y, io_dtype == SD_F32, ctx, Tc, Dc, ln_gamma, ln_beta, ln_eps, *q, *k, *v, *o, Bn, T, C, heads, aw,
-                         static_cast<hipStream_t>(stream));
+                         static_cast<hipStream_t>(stream), nullptr, false, &dep);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -422,7 +492,7 @@ extern "C" size_t sd_ff_block_workspace_bytes(int32_t M, int32_t C, int32_t F, i
     Workspace ws((void*)256, (size_t)-1 / 2);
     FfWs w;
     carve_ff(ws, w, M, C, F, r_max);
-    return ws.used;
+    return ws.used + DepFlags::bytes_for(M);
 }
 
 extern "C" int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype, const uint16_t* ln_gamma, const uint16_t* ln_beta,
@@ -438,8 +508,11 @@ extern "C" int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype, const u
     const sd_proj* ps[2] = {ff1, ff2};
     Workspace w(ws, ws_bytes);
     FfWs fw;
-    SD_REQUIRE(ws && carve_ff(w, fw, M, C, F, rmax_of(ps, 2)), SD_EWORKSPACE, "ff_block: workspace of %zu bytes is too small", ws_bytes);
-    return ff_sublayer(x, y, io_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, *ff1, *ff2, M, C, F, fw, static_cast<hipStream_t>(stream));
+    DepFlags dep;
+    SD_REQUIRE(ws && carve_ff(w, fw, M, C, F, rmax_of(ps, 2)) && dep.carve(w, M), SD_EWORKSPACE, "ff_block: workspace of %zu bytes is too small", ws_bytes);
+    int rc2 = dep.clear(static_cast<hipStream_t>(stream));
+    if (rc2) return rc2;
+    return ff_sublayer(x, y, io_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, *ff1, *ff2, M, C, F, fw, static_cast<hipStream_t>(stream), &dep);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -476,7 +549,7 @@ extern "C" int sd_groupnorm_silu_fwd(const uint16_t* x, uint16_t* y, const uint1
 // spatial_transformer_fwd
 // ---------------------------------------------------------------------------------------
 namespace sd {
-struct StackWs { float* h; uint16_t* g; float* gn; AttnWs a; FfWs f; };
+struct StackWs { float* h; uint16_t* g; float* gn; AttnWs a; FfWs f; DepFlags dep; };
 static bool carve_stack(Workspace& ws, StackWs& w, int Bn, int T, int C, int Tc, int rmax) {
     const size_t M = (size_t)Bn * T;
     w.h = (float*)ws.take(M * C * 4);
@@ -484,6 +557,7 @@ static bool carve_stack(Workspace& ws, StackWs& w, int Bn, int T, int C, int Tc,
     w.gn = (float*)ws.take(groupnorm_partials_bytes(Bn, T, 32));
     carve_attn(ws, w.a, Bn, T, C, Tc > T ? Tc : T, rmax, C / 64, Tc);
     carve_ff(ws, w.f, (int)M, C, 4 * C, rmax);
+    w.dep.carve(ws, std::max(M, (size_t)Bn * Tc));
     return ws.ok();
 }
 }  // namespace sd
@@ -533,22 +607,23 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
     // GroupNorm -> proj_in -> fp32 residual stream h
     if ((rc = launch_groupnorm(x, sw.g, p->gn_g, p->gn_b, Bn, T, C, 32, 1e-6f, sw.gn, s))) return rc;
     ProjCall cin = {sw.g, C, M, C, C, &p->proj_in, sw.f.t1, {sw.h, C, 1, nullptr, 0, false, 0}};
-    if ((rc = run_projections(&cin, 1, s))) return rc;
+    if ((rc = sw.dep.clear(s))) return rc;
+    if ((rc = run_projections(&cin, 1, s, -1, &sw.dep))) return rc;
     for (int i = 0; i < p->depth; ++i) {
         const sd_block_params& b = p->blocks[i];
         // the text keys / values of this block's cross-attention ride in the self-attention launches
         std::vector<ProjCall> ahead;
         push_kv_calls(ahead, ctx, Dc, Tc, b.k2, b.v2, sw.a.k2, sw.a.vt2, sw.a.tk2, sw.a.tv2, Bn, C);
-        if ((rc = attn_sublayer(sw.h, sw.h, 1, nullptr, 0, 0, b.ln1_g, b.ln1_b, 1e-5f, b.q1, b.k1, b.v1, b.o1, Bn, T, C, heads, sw.a, s, &ahead)))
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, nullptr, 0, 0, b.ln1_g, b.ln1_b, 1e-5f, b.q1, b.k1, b.v1, b.o1, Bn, T, C, heads, sw.a, s, &ahead, false, &sw.dep)))
             return rc;
-        if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s, nullptr, true)))
+        if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s, nullptr, true, &sw.dep)))
             return rc;
-        if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s))) return rc;
+        if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s, &sw.dep))) return rc;
     }
     // proj_out + input residual, bf16 out
     if ((rc = launch_cvt_f32_to_bf16(sw.h, sw.g, (size_t)M * C, s))) return rc;
     ProjCall cout = {sw.g, C, M, C, C, &p->proj_out, sw.f.t1, {y, C, 0, x, C, false, 0}};
-    return run_projections(&cout, 1, s);
+    return run_projections(&cout, 1, s, -1, &sw.dep);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -122,18 +122,36 @@ struct GemmProblem {
     int32_t bias_on_rows;
     float alpha;
     int32_t tile_begin, tiles_m, tiles_n;      // filled by the launcher
+    // Dependencies inside one launch (a down-projection and the base GEMM that reads it as its
+    // second K segment).  signal: every finished tile of this problem adds 1 to
+    // signal[row-tile index]; its y is bf16 without residual.  wait: before loading K segment 1
+    // a tile waits until wait[i] >= wait_need for every row-tile i of the producer that covers
+    // its P rows (or its Q rows if wait_cols).  Flags are zero when the launch starts.
+    int32_t* signal;
+    const int32_t* wait;
+    int32_t wait_need;                         // filled by the launcher
+    int32_t wait_cols;
 };
 
 constexpr int GEMM_MAX_PROBLEMS = 16;
 struct GemmGroup {
     int32_t n;
     int32_t total_tiles;
+    int32_t n_lead;                          // tiles of the signalling problems (first in the group), filled by the launcher
+    int32_t zero_n;                          // the launch also clears zero_ptr[0 .. zero_n): the flags of the next launch
+    int32_t* zero_ptr;
     int32_t first_tile[GEMM_MAX_PROBLEMS];   // copy of p[i].tile_begin, read by every workgroup in one scalar load
     GemmProblem p[GEMM_MAX_PROBLEMS];
 };
 
-// Launch every problem of `g` in one grid.  Problems must all be GEGLU or all plain.
+// Launch every problem of `g` in one grid.  Problems must all be GEGLU or all plain; signalling
+// problems come first and every problem that waits on one is in the same group.
 int launch_gemm_group(GemmGroup& g, hipStream_t stream);
+// n zeros at p (the flags of the first dependent launch of a call)
+int launch_clear_flags(int32_t* p, int n, hipStream_t stream);
+// number of tiles, since the library was loaded, that gave up waiting for a flag (0 unless the
+// in-launch dependency protocol is broken); synchronises the device
+int gemm_dep_timeouts(long long* count);
 
 // LayerNorm rows of x [M, C] (fp32 or bf16) -> bf16.
 int launch_layernorm(const void* x, int x_f32, const uint16_t* gamma, const uint16_t* beta, float eps,

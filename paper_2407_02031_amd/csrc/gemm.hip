@@ -52,14 +52,28 @@ __device__ __attribute__((aligned(256))) uint32_t g_gemm_zeros[64];
 // Written as inline assembly so that the compiler does not serialise the LDS reads of the
 // tile being multiplied behind loads that target another ring stage; completion is tracked
 // by hand with vmcnt (loads retire in order) and a workgroup barrier.
+// DEV: the load is of device scope (it must observe data that a workgroup on another XCD, with
+// its own L2, wrote during this launch with device-scope stores).
+template <bool DEV = false>
 __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr) : "memory", "m0");
+    if (DEV)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off sc1" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(gptr) : "memory", "m0");
 }
 // Same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane, which
 // keeps the per-step address arithmetic on the scalar unit.
+template <bool DEV = false>
 __device__ __forceinline__ void dma16_so(const void* sbase, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
+    if (DEV)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 sc1" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(uniform_ptr(sbase)) : "memory", "m0");
 }
+// Tiles that gave up waiting for a producer's flag (never, unless the dependency protocol is
+// broken): the wait is bounded so that every wavefront exits whatever happens.
+__device__ unsigned long long g_gemm_dep_timeouts = 0;
+constexpr int DEP_SPIN_LIMIT = 1 << 19;
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -104,11 +118,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     // contiguous range of tiles, and order tiles inside a problem in bands of 8 row-tiles
     // (row-tile index fastest), so that the workgroups resident on one XCD share a small set
     // of activation rows and weight rows.
+    // The tiles of signalling problems (down-projections that tiles of this same launch wait
+    // for) come first and are dealt round-robin: they are the first workgroups dispatched on
+    // every XCD, so all of them are running, or done, before any tile can wait for them.
     int tile = blockIdx.x;
     {
-        const int total = gridDim.x;
-        if ((total & 7) == 0) tile = (tile & 7) * (total >> 3) + (tile >> 3);
+        const int lead = g.n_lead;
+        const int rest = (int)gridDim.x - lead;
+        if (tile >= lead && (rest & 7) == 0) {
+            const int r = tile - lead;
+            tile = lead + (r & 7) * (rest >> 3) + (r >> 3);
+        }
     }
+    if (blockIdx.x == gridDim.x - 1)   // flags of the next dependent launch: nothing reads them before this kernel ends
+        for (int i = threadIdx.x; i < g.zero_n; i += 64 * NW) g.zero_ptr[i] = 0;
     // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
     // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
     // problem pay a second round.
@@ -132,6 +155,21 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, hi = lane >> 5;
     const int wm = (wave / WGN) * WM, wn = (wave % WGN) * WN;
+
+    // ---- dependency on a producer problem of this launch.  The flags are read once now (the
+    // answer arrives with the first operand tile); tiles that start after the producer has
+    // finished, the usual case, never look again.  Device-scope loads: the producer's tile may
+    // have run on another XCD.
+    const int32_t* const wflag = K1 ? P.wait : nullptr;
+    const int32_t* fptr = nullptr;
+    int f_early = 0;
+    if (wflag) {
+        const int lo = P.wait_cols ? n0 : m0;
+        const int hi = P.wait_cols ? min(n0 + BN_OUT, N) : min(m0 + BM, Mp);
+        const int f0 = lo / BM, f1 = (hi - 1) / BM;
+        fptr = wflag + f0 + min(lane, f1 - f0);
+        f_early = __hip_atomic_load(fptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     // Q-operand (weight) row of tile row j.  GEGLU: 32-row blocks alternate value / gate
     // rows of the same 32 output columns, so one lane ends up holding both halves.
@@ -187,6 +225,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     // issue the loads of k-step t into ring stage `stg`.  A partial last tile of a segment
     // (GUARD only) takes per-lane 64-bit addresses so that chunks past the segment's end can
     // point at the zero page.
+    bool dep_ready = wflag == nullptr;
     auto issue_tile = [&](int t, int stg) {
         const bool s1 = t >= nk0;
         const int kb = (s1 ? t - nk0 : t) * BK;
@@ -194,17 +233,37 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
         const uint32_t sbase = wave_base + (uint32_t)stg * (STAGE * 16);
         const uint16_t* pb = (s1 ? pb1 : pb0) + kb;
         const uint16_t* qb = (s1 ? qb1 : qb0) + kb;
+        const bool dev = s1 && wflag;   // segment 1 was written during this launch
+        if (dev && !dep_ready) {
+            // the producer's tiles were dispatched before this one and wait for nothing, so
+            // this ends; the bound is there so that it ends even if that reasoning is wrong
+            for (int spins = 0;; ++spins) {
+                const int v = __hip_atomic_load(fptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__all(v >= P.wait_need)) break;
+                if (spins >= DEP_SPIN_LIMIT) {
+                    if (tid == 0) atomicAdd(&g_gemm_dep_timeouts, 1ull);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(8);
+            }
+            dep_ready = true;
+        }
         if (GUARD && kb + BK > Kseg) {
 #pragma unroll
             for (int j = 0; j < LPT; ++j) {
                 const char* src = reinterpret_cast<const char*>(j < JP ? pb : qb) + (s1 ? off1[j] : off0[j]);
                 src = (kb + kcol[GUARD ? j : 0] < Kseg) ? src : reinterpret_cast<const char*>(g_gemm_zeros);
-                dma16(src, sbase + (uint32_t)j * (NW * 1024));
+                if (dev) dma16<true>(src, sbase + (uint32_t)j * (NW * 1024));
+                else dma16<false>(src, sbase + (uint32_t)j * (NW * 1024));
             }
+        } else if (dev) {
+#pragma unroll
+            for (int j = 0; j < LPT; ++j)
+                dma16_so<true>(j < JP ? pb : qb, off1[j], sbase + (uint32_t)j * (NW * 1024));
         } else {
 #pragma unroll
             for (int j = 0; j < LPT; ++j)
-                dma16_so(j < JP ? pb : qb, s1 ? off1[j] : off0[j], sbase + (uint32_t)j * (NW * 1024));
+                dma16_so<false>(j < JP ? pb : qb, s1 ? off1[j] : off0[j], sbase + (uint32_t)j * (NW * 1024));
         }
     };
 
@@ -254,6 +313,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
 #pragma unroll
     for (int d = 0; d < DIST; ++d)
         if (d < nkt) issue_tile(d, d);
+    if (!dep_ready) dep_ready = __all(f_early >= P.wait_need);
 
     // ---- main loop.  Step t: wait until this wave's loads of tile t have landed (loads of
     // newer tiles may stay in flight), barrier (every wave's part of tile t is in LDS and
@@ -328,6 +388,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
     const float alpha = P.alpha;
     const uint16_t* bias = P.bias;
+    int32_t* const sig = P.signal;
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -395,7 +456,11 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
                             bf16x4 o;
 #pragma unroll
                             for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
-                            *reinterpret_cast<bf16x4*>(yp) = o;
+                            if (sig)   // device-scope store: read by tiles of this launch on other XCDs
+                                __hip_atomic_store(reinterpret_cast<uint64_t*>(yp), __builtin_bit_cast(uint64_t, o), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                            else
+                                *reinterpret_cast<bf16x4*>(yp) = o;
                         } else {
 #pragma unroll
                             for (int e = 0; e < 4; ++e)
@@ -411,12 +476,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
             __builtin_amdgcn_wave_barrier();
         }
     }
+    // ---- tell the tiles that wait for this one: every wave's stores have completed at device
+    // scope (vmcnt counts a device-scope store until it is visible there), then one flag add
+    if (sig) {
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (tid == 0) __hip_atomic_fetch_add(sig + tm, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool RES32>
 static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
     int total = 0;
+    g.n_lead = 0;
     for (int i = 0; i < g.n; ++i) {
         GemmProblem& P = g.p[i];
         P.tiles_m = (P.Mp + BM - 1) / BM;
@@ -424,6 +497,8 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
         P.tile_begin = total;
         g.first_tile[i] = total;
         total += P.tiles_m * P.tiles_n;
+        if (P.signal) g.n_lead = total;
+        P.wait_need = (P.K1 + BN_OUT - 1) / BN_OUT;   // column tiles of the producer, whose N is this problem's K1
     }
     g.total_tiles = total;
     if (total == 0) return SD_OK;
@@ -456,6 +531,12 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         SD_REQUIRE(P.ldp0 > 0 && P.ldq0 > 0 && P.ldp0 * 256 < (1ll << 31) && P.ldq0 * span < (1ll << 31) &&
                        (P.K1 == 0 || (P.ldp1 > 0 && P.ldq1 > 0 && P.ldp1 * 256 < (1ll << 31) && P.ldq1 * span < (1ll << 31))),
                    SD_EINVAL, "gemm problem %d: leading dimension out of range", i);
+        if (P.signal) {
+            SD_REQUIRE(i == 0 || g.p[i - 1].signal, SD_EINVAL, "gemm group: signalling problem %d after a plain one", i);
+            SD_REQUIRE(!P.y_f32 && !P.res && !P.wait && P.N % 4 == 0 && P.ldy % 4 == 0 && !geglu, SD_EINVAL,
+                       "gemm problem %d: a signalling problem stores plain bf16 rows", i);
+        }
+        SD_REQUIRE(!P.wait || (P.K1 > 0 && g.p[0].signal), SD_EINVAL, "gemm problem %d waits but the group has no producer", i);
         if (P.Mp == 0 || P.N == 0) continue;
         if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
         if (P.N > maxN) maxN = P.N;
@@ -484,6 +565,23 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     if (geglu) return launch_cfg<128, 128, 64, 4, 2, 2, true, false>(g, guard, stream);
     if (res32) return launch_cfg<128, 128, 64, 4, 2, 2, false, true>(g, guard, stream);
     return launch_cfg<128, 128, 64, 4, 2, 2, false, false>(g, guard, stream);
+}
+
+__global__ void clear_flags_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+int launch_clear_flags(int32_t* p, int n, hipStream_t stream) {
+    if (n <= 0) return SD_OK;
+    hipLaunchKernelGGL(clear_flags_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, p, n);
+    SD_HIP_CHECK(hipGetLastError());
+    return SD_OK;
+}
+int gemm_dep_timeouts(long long* count) {
+    unsigned long long v = 0;
+    SD_HIP_CHECK(hipMemcpyFromSymbol(&v, HIP_SYMBOL(g_gemm_dep_timeouts), sizeof(v)));
+    *count = (long long)v;
+    return SD_OK;
 }
 
 }  // namespace sd

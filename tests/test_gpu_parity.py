@@ -72,6 +72,30 @@ def test_lora_linear_matches_oracle(B, M, K, N, rank, scale):
         assert rel_err(host(ym), ref) <= 2 * BF16_TOL     # W' itself is rounded to bf16 here
 
 
+def test_lora_linear_same_workspace_new_inputs(B):
+    """The base GEMM's tiles read the down-projection that other tiles of the same launch
+    wrote moments before, possibly on another XCD with its own L2.  Reusing one workspace with
+    changing inputs and adapters would serve a stale down-projection (the previous call's, still
+    cached) if those reads and writes were not of device scope; a tile that did not wait at all
+    would read the previous call's too.  Large enough that every XCD runs tiles of both kinds."""
+    import torch
+    M, K, N, rank = 4096 + 37, 640, 640, 64
+    r = rng(99)
+    need = B.lib().sd_lora_linear_workspace_bytes(M, N, K, rank, 0)
+    ws = torch.zeros(need, dtype=torch.uint8, device="cuda")
+    for trial in range(4):
+        p = mkproj(r, N, K, rank, bias=True, scale=1.0 + trial)
+        x = G.bf16_round(r.standard_normal((M, K)).astype(np.float32))
+        ref = O.lora_linear(x, p["W"], p["b"], p["A"], p["B"], p["scale"])
+        base = O.linear(x, p["W"], p["b"])
+        assert rel_err(base, ref) > 10 * BF16_TOL          # the adapter term carries most of the output
+        xd, pd = dev(x, B), B.Proj.from_numpy(p)
+        for rep in range(3):
+            y = B.lora_linear_fwd(xd, pd, ws=ws)
+            assert rel_err(host(y), ref) <= BF16_TOL, (trial, rep)
+    assert B.gemm_dep_timeouts() == 0
+
+
 def test_lora_linear_layernorm_residual_fp32(B):
     import torch
     r = rng(7)
@@ -487,3 +511,9 @@ def test_stack_graph_replay_matches_eager(B):
         # eager work between replays
         again = B.spatial_transformer_fwd(x, ctx, sp, cfg.heads, ws=ws)
         assert torch.equal(again, y_eager)
+
+
+def test_zz_no_tile_gave_up_waiting(B):
+    """Runs last in this file: across everything above, no base-GEMM tile ran out of spins
+    while waiting for a down-projection tile of its own launch."""
+    assert B.gemm_dep_timeouts() == 0
