@@ -6,6 +6,7 @@
 #include <stddef.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <type_traits>
 
 #include "../../include/swiftdiff.h"
 

@@ -79,11 +79,24 @@ __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
+// Tiles of signalling problems (down-projections, N = rank) run a body of their own inside the
+// same kernel: BN = 64 instead of the launch's BN, which frees LDS for a deeper ring.  Other
+// tiles of the launch wait for these, and what a down-projection tile spends is latency per
+// k-step, so tiles in flight are what shortens it.
+constexpr int DOWN_BN = 64;
+template <int BM, int BN, int BK, int STAGES>
+constexpr int down_stages() {
+    if (BN <= DOWN_BN) return STAGES;
+    const int fit = STAGES * (BM + BN) / (BM + DOWN_BN);   // stages of the narrower tile in the same bytes
+    return fit > 5 ? 5 : (fit < 3 ? 3 : fit);
+}
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES>
 constexpr int gemm_lds_chunks() {
     constexpr int ring = STAGES * (BM + BN) * (BK / 8);
+    constexpr int dring = down_stages<BM, BN, BK, STAGES>() * (BM + (BN < DOWN_BN ? BN : DOWN_BN)) * (BK / 8);
     constexpr int epi = WGM * WGN * 32 * EPI_STRIDE / 4;
-    return ring > epi ? ring : epi;
+    constexpr int m = ring > dring ? ring : dring;
+    return m > epi ? m : epi;
 }
 
 // GUARD: K segments that are not multiples of 64 (tail chunks read zeros).
@@ -95,7 +108,7 @@ constexpr int gemm_min_waves() {
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD, bool RES32>
-__global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WGN, STAGES>())) void gemm_kernel(const GemmGroup g) {
+__device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, u32x4* const lds) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -111,36 +124,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     static_assert(!GEGLU || (NI % 2 == 0), "GEGLU needs value/gate column-block pairs per wave");
     static_assert(DIST >= 1 && DIST <= 4, "ring depth");
 
-    __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, BK, WGM, WGN, STAGES>()];
-
-    // ---- which problem, which tile ----
-    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
-    // contiguous range of tiles, and order tiles inside a problem in bands of 8 row-tiles
-    // (row-tile index fastest), so that the workgroups resident on one XCD share a small set
-    // of activation rows and weight rows.
-    // The tiles of signalling problems (down-projections that tiles of this same launch wait
-    // for) come first and are dealt round-robin: they are the first workgroups dispatched on
-    // every XCD, so all of them are running, or done, before any tile can wait for them.
-    int tile = blockIdx.x;
-    {
-        const int lead = g.n_lead;
-        const int rest = (int)gridDim.x - lead;
-        if (tile >= lead && (rest & 7) == 0) {
-            const int r = tile - lead;
-            tile = lead + (r & 7) * (rest >> 3) + (r >> 3);
-        }
-    }
-    if (blockIdx.x == gridDim.x - 1)   // flags of the next dependent launch: nothing reads them before this kernel ends
-        for (int i = threadIdx.x; i < g.zero_n; i += 64 * NW) g.zero_ptr[i] = 0;
-    // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
-    // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
-    // problem pay a second round.
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < GEMM_MAX_PROBLEMS; ++i)
-        if (i < g.n && tile >= g.first_tile[i]) pi = i;
-    GemmProblem P = g.p[0];
-    if (pi != 0) P = g.p[pi];
+    // ---- which tile of the problem ----
     const int local = tile - P.tile_begin;
     const int band_tiles = 8 * P.tiles_n;
     const int band = local / band_tiles, rem = local - band * band_tiles;
@@ -485,6 +469,47 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     }
 }
 
+template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD, bool RES32>
+__global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WGN, STAGES>())) void gemm_kernel(const GemmGroup g) {
+    constexpr int NW = WGM * WGN;
+    __shared__ u32x4 lds[gemm_lds_chunks<BM, BN, BK, WGM, WGN, STAGES>()];
+    // ---- which problem, which tile ----
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Give every XCD a
+    // contiguous range of tiles, and order tiles inside a problem in bands of 8 row-tiles
+    // (row-tile index fastest), so that the workgroups resident on one XCD share a small set
+    // of activation rows and weight rows.
+    // The tiles of signalling problems (down-projections that tiles of this same launch wait
+    // for) come first and are dealt round-robin: they are the first workgroups dispatched on
+    // every XCD, so all of them are running, or done, before any tile can wait for them.
+    int tile = blockIdx.x;
+    {
+        const int lead = g.n_lead;
+        const int rest = (int)gridDim.x - lead;
+        if (tile >= lead && (rest & 7) == 0) {
+            const int r = tile - lead;
+            tile = lead + (r & 7) * (rest >> 3) + (r >> 3);
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1)   // flags of the next dependent launch: nothing reads them before this kernel ends
+        for (int i = threadIdx.x; i < g.zero_n; i += 64 * NW) g.zero_ptr[i] = 0;
+    // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
+    // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
+    // problem pay a second round.
+    int pi = 0;
+#pragma unroll
+    for (int i = 1; i < GEMM_MAX_PROBLEMS; ++i)
+        if (i < g.n && tile >= g.first_tile[i]) pi = i;
+    GemmProblem P = g.p[0];
+    if (pi != 0) P = g.p[pi];
+    if constexpr (BN > DOWN_BN && !GEGLU) {
+        if (P.signal) {
+            gemm_tile<BM, DOWN_BN, BK, WGM, WGN, down_stages<BM, BN, BK, STAGES>(), false, GUARD, false>(P, tile, lds);
+            return;
+        }
+    }
+    gemm_tile<BM, BN, BK, WGM, WGN, STAGES, GEGLU, GUARD, RES32>(P, tile, lds);
+}
+
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool RES32>
 static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     constexpr int BN_OUT = GEGLU ? BN / 2 : BN;
@@ -493,12 +518,12 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
     for (int i = 0; i < g.n; ++i) {
         GemmProblem& P = g.p[i];
         P.tiles_m = (P.Mp + BM - 1) / BM;
-        P.tiles_n = (P.N + BN_OUT - 1) / BN_OUT;
+        P.tiles_n = P.signal ? (P.N + (BN < DOWN_BN ? BN : DOWN_BN) - 1) / (BN < DOWN_BN ? BN : DOWN_BN) : (P.N + BN_OUT - 1) / BN_OUT;
         P.tile_begin = total;
         g.first_tile[i] = total;
         total += P.tiles_m * P.tiles_n;
         if (P.signal) g.n_lead = total;
-        P.wait_need = (P.K1 + BN_OUT - 1) / BN_OUT;   // column tiles of the producer, whose N is this problem's K1
+        P.wait_need = (P.K1 + (BN < DOWN_BN ? BN : DOWN_BN) - 1) / (BN < DOWN_BN ? BN : DOWN_BN);   // column tiles of the producer, whose N is this problem's K1
     }
     g.total_tiles = total;
     if (total == 0) return SD_OK;
