@@ -147,8 +147,8 @@ struct DepFlags {
 // Run independent projections.  With flags, as one launch: down-projection tiles first, and a
 // base GEMM tile waits for the down-projection rows it reads just before its second K segment
 // (by then they are long done, except in the first round of workgroups).  Without, or when the
-// projections do not fit one group or include a GEGLU, as two rounds of launches: every
-// down-projection, then every base GEMM.
+// projections do not fit one group, as two rounds of launches: every down-projection, then
+// every base GEMM.
 static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1, DepFlags* dep = nullptr) {
     GemmGroup g;
     memset(&g, 0, sizeof(g));
@@ -156,14 +156,12 @@ static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int
     if (dep && dep->f[0]) {
         int problems = 0, downs = 0;
         size_t flags = 0;
-        bool geglu = false;
         for (int i = 0; i < n; ++i) {
             if (calls[i].M <= 0) continue;
             ++problems;
-            if (calls[i].o.geglu_F > 0) geglu = true;
             if (calls[i].p->r > 0) { ++problems; ++downs; flags += ((size_t)calls[i].M + 63) / 64; }
         }
-        if (downs > 0 && problems <= GEMM_MAX_PROBLEMS && flags <= (size_t)dep->cap && !geglu) {
+        if (downs > 0 && problems <= GEMM_MAX_PROBLEMS && flags <= (size_t)dep->cap) {
             int32_t* const base = dep->f[dep->turn];
             std::vector<int32_t*> slot(n, nullptr);
             size_t used = 0;
@@ -413,7 +411,7 @@ extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj*
     DepFlags dep;
     if (p->r > 0) dep.carve(w, M);
     SD_REQUIRE(w.ok(), SD_EWORKSPACE, "lora_linear: workspace too small");
-    if (p->r > 0 && epilogue != SD_EPI_GEGLU && (rc = dep.clear(s))) return rc;
+    if (p->r > 0 && (rc = dep.clear(s))) return rc;
     ProjCall c = {xin, K, M, K, N, p, t, {y, N, y_dtype == SD_F32, residual, N, false, epilogue == SD_EPI_GEGLU ? N : 0}};
     return run_projections(&c, 1, s, -1, &dep);
 }

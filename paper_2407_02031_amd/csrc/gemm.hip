@@ -501,7 +501,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
         if (i < g.n && tile >= g.first_tile[i]) pi = i;
     GemmProblem P = g.p[0];
     if (pi != 0) P = g.p[pi];
-    if constexpr (BN > DOWN_BN && !GEGLU) {
+    if constexpr (BN > DOWN_BN) {
         if (P.signal) {
             gemm_tile<BM, DOWN_BN, BK, WGM, WGN, down_stages<BM, BN, BK, STAGES>(), false, GUARD, false>(P, tile, lds);
             return;
@@ -537,7 +537,8 @@ static int launch_cfg(GemmGroup& g, bool guard, hipStream_t stream) {
 
 int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     SD_REQUIRE(g.n >= 1 && g.n <= GEMM_MAX_PROBLEMS, SD_EINVAL, "gemm group: %d problems", g.n);
-    bool geglu = g.p[0].geglu_F > 0;
+    bool geglu = false;   // a GEGLU group: GEGLU problems plus, possibly, the plain down-projections they wait for
+    for (int i = 0; i < g.n; ++i) geglu = geglu || g.p[i].geglu_F > 0;
     bool guard = false;
     int maxN = 0;
     long t128 = 0;        // workgroup tiles at 128x128
@@ -545,7 +546,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
         if (P.res && P.y_f32 && P.Mp > 0 && P.N > 0) res32 = true;
-        SD_REQUIRE((P.geglu_F > 0) == geglu, SD_EINVAL, "gemm group mixes GEGLU and plain problems");
+        SD_REQUIRE((P.geglu_F > 0) == geglu || P.signal, SD_EINVAL, "gemm group mixes GEGLU and plain problems");
         SD_REQUIRE(P.Mp >= 0 && P.N >= 0 && P.K0 > 0 && P.K0 % 8 == 0 && P.K1 >= 0 && P.K1 % 8 == 0, SD_EINVAL,
                    "gemm problem %d: bad sizes M=%d N=%d K0=%d K1=%d", i, P.Mp, P.N, P.K0, P.K1);
         SD_REQUIRE(P.p0 && P.q0 && P.y && (P.K1 == 0 || (P.p1 && P.q1)), SD_EINVAL, "gemm problem %d: null operand", i);
@@ -558,7 +559,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
                    SD_EINVAL, "gemm problem %d: leading dimension out of range", i);
         if (P.signal) {
             SD_REQUIRE(i == 0 || g.p[i - 1].signal, SD_EINVAL, "gemm group: signalling problem %d after a plain one", i);
-            SD_REQUIRE(!P.y_f32 && !P.res && !P.wait && P.N % 4 == 0 && P.ldy % 4 == 0 && !geglu, SD_EINVAL,
+            SD_REQUIRE(!P.y_f32 && !P.res && !P.wait && P.N % 4 == 0 && P.ldy % 4 == 0 && P.geglu_F == 0, SD_EINVAL,
                        "gemm problem %d: a signalling problem stores plain bf16 rows", i);
         }
         SD_REQUIRE(!P.wait || (P.K1 > 0 && g.p[0].signal), SD_EINVAL, "gemm problem %d waits but the group has no producer", i);
