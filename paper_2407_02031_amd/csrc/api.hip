@@ -131,6 +131,7 @@ struct DepFlags {
     int32_t* f[2] = {nullptr, nullptr};
     int cap = 0;
     int turn = 0;
+    bool pending = false;   // f[0] still has to be cleared: by the next LayerNorm launch, or by a launch of its own
     static int cap_for(size_t rows) { return (int)(4 * ((rows + 63) / 64) + 64); }
     static size_t bytes_for(size_t rows) { return round_up((size_t)cap_for(rows) * 4, 256) * 2; }
     bool carve(Workspace& ws, size_t rows) {
@@ -141,8 +142,23 @@ struct DepFlags {
         turn = 0;
         return b != nullptr;
     }
-    int clear(hipStream_t stream) { turn = 0; return launch_clear_flags(f[0], cap, stream); }
+    void reset() { turn = 0; pending = f[0] != nullptr; }
+    int clear_now(hipStream_t stream) {
+        if (!pending) return SD_OK;
+        pending = false;
+        return launch_clear_flags(f[0], cap, stream);
+    }
 };
+
+// LayerNorm that also clears the first flag array of the call if that is still due
+static int layernorm(const void* x, int x_f32, const uint16_t* g, const uint16_t* b, float eps, uint16_t* y, int M, int C,
+                     hipStream_t stream, DepFlags* dep) {
+    if (dep && dep->pending && M > 0) {
+        dep->pending = false;
+        return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream, dep->f[0], dep->cap);
+    }
+    return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream);
+}
 
 // Run independent projections.  With flags, as one launch: down-projection tiles first, and a
 // base GEMM tile waits for the down-projection rows it reads just before its second K segment
@@ -162,6 +178,7 @@ static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int
             if (calls[i].p->r > 0) { ++problems; ++downs; flags += ((size_t)calls[i].M + 63) / 64; }
         }
         if (downs > 0 && problems <= GEMM_MAX_PROBLEMS && flags <= (size_t)dep->cap) {
+            if ((rc = dep->clear_now(stream))) return rc;
             int32_t* const base = dep->f[dep->turn];
             std::vector<int32_t*> slot(n, nullptr);
             size_t used = 0;
@@ -256,7 +273,7 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     const int Tk = ctx ? Tc : T;
     const int Kkv = ctx ? Dc : C;
     const int Tkp = pad8(Tk);
-    int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
+    int rc = layernorm(x, io_f32, g, b, eps, w.n, M, C, stream, dep);
     if (rc) return rc;
     const uint16_t* src = ctx ? ctx : w.n;
     std::vector<ProjCall> calls;
@@ -297,7 +314,7 @@ static bool carve_ff(Workspace& ws, FfWs& w, int M, int C, int F, int rmax) {
 
 static int ff_sublayer(const void* x, void* y, int io_f32, const uint16_t* g, const uint16_t* b, float eps,
                        const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream, DepFlags* dep = nullptr) {
-    int rc = launch_layernorm(x, io_f32, g, b, eps, w.n, M, C, stream);
+    int rc = layernorm(x, io_f32, g, b, eps, w.n, M, C, stream, dep);
     if (rc) return rc;
     ProjCall c1 = {w.n, C, M, C, F, &p1, w.t1, {w.g, F, 0, nullptr, 0, false, F}};
     if ((rc = run_projections(&c1, 1, stream, SD_TIMING_FF1, dep))) return rc;
@@ -402,16 +419,16 @@ extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj*
     hipStream_t s = static_cast<hipStream_t>(stream);
     Workspace w(ws, ws_bytes);
     const uint16_t* xin = static_cast<const uint16_t*>(x);
-    if (has_ln) {
-        uint16_t* n = (uint16_t*)w.take((size_t)M * K * 2);
-        if ((rc = launch_layernorm(x, x_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, n, M, K, s))) return rc;
-        xin = n;
-    }
+    uint16_t* n = has_ln ? (uint16_t*)w.take((size_t)M * K * 2) : nullptr;
     uint16_t* t = (uint16_t*)w.take((size_t)M * (p->r > 0 ? p->r : 8) * 2);
     DepFlags dep;
     if (p->r > 0) dep.carve(w, M);
     SD_REQUIRE(w.ok(), SD_EWORKSPACE, "lora_linear: workspace too small");
-    if (p->r > 0 && (rc = dep.clear(s))) return rc;
+    dep.reset();
+    if (has_ln) {
+        if ((rc = layernorm(x, x_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, n, M, K, s, &dep))) return rc;
+        xin = n;
+    }
     ProjCall c = {xin, K, M, K, N, p, t, {y, N, y_dtype == SD_F32, residual, N, false, epilogue == SD_EPI_GEGLU ? N : 0}};
     return run_projections(&c, 1, s, -1, &dep);
 }
@@ -477,7 +494,7 @@ extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const
     DepFlags dep;
     SD_REQUIRE(ws && carve_attn(w, aw, Bn, T, C, Tk, rmax, heads) && dep.carve(w, (size_t)Bn * (Tk > T ? Tk : T)), SD_EWORKSPACE,
                "attn_block: workspace of %zu bytes is too small", ws_bytes);
-    if ((rc = dep.clear(static_cast<hipStream_t>(stream)))) return rc;
+    dep.reset();
     return attn_sublayer(x, y, io_dtype == SD_F32, ctx, Tc, Dc, ln_gamma, ln_beta, ln_eps, *q, *k, *v, *o, Bn, T, C, heads, aw,
                          static_cast<hipStream_t>(stream), nullptr, false, &dep);
 }
@@ -508,8 +525,7 @@ extern "C" int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype, const u
     FfWs fw;
     DepFlags dep;
     SD_REQUIRE(ws && carve_ff(w, fw, M, C, F, rmax_of(ps, 2)) && dep.carve(w, M), SD_EWORKSPACE, "ff_block: workspace of %zu bytes is too small", ws_bytes);
-    int rc2 = dep.clear(static_cast<hipStream_t>(stream));
-    if (rc2) return rc2;
+    dep.reset();
     return ff_sublayer(x, y, io_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, *ff1, *ff2, M, C, F, fw, static_cast<hipStream_t>(stream), &dep);
 }
 
@@ -605,7 +621,7 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
     // GroupNorm -> proj_in -> fp32 residual stream h
     if ((rc = launch_groupnorm(x, sw.g, p->gn_g, p->gn_b, Bn, T, C, 32, 1e-6f, sw.gn, s))) return rc;
     ProjCall cin = {sw.g, C, M, C, C, &p->proj_in, sw.f.t1, {sw.h, C, 1, nullptr, 0, false, 0}};
-    if ((rc = sw.dep.clear(s))) return rc;
+    sw.dep.reset();
     if ((rc = run_projections(&cin, 1, s, -1, &sw.dep))) return rc;
     for (int i = 0; i < p->depth; ++i) {
         const sd_block_params& b = p->blocks[i];

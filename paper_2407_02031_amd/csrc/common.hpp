@@ -155,8 +155,9 @@ int launch_clear_flags(int32_t* p, int n, hipStream_t stream);
 int gemm_dep_timeouts(long long* count);
 
 // LayerNorm rows of x [M, C] (fp32 or bf16) -> bf16.
+// zero_ptr[0 .. zero_n) is cleared by the same launch (dependency flags of a later launch)
 int launch_layernorm(const void* x, int x_f32, const uint16_t* gamma, const uint16_t* beta, float eps,
-                     uint16_t* y, int M, int C, hipStream_t stream);
+                     uint16_t* y, int M, int C, hipStream_t stream, int32_t* zero_ptr = nullptr, int zero_n = 0);
 // fp32 [n] -> bf16, bf16 -> fp32 converters for the stack boundary
 int launch_cvt_bf16_to_f32(const uint16_t* x, float* y, size_t n, hipStream_t stream);
 int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t stream);

@@ -10,84 +10,115 @@ namespace sd {
 // ---------------------------------------------------------------------------------------
 constexpr int LN_MAXJ = 8;   // float4 chunks per lane: 64 lanes * 4 * 8 = 2048 channels
 
-template <bool XF32>
+// JN: chunks per lane the row needs (C <= 256 * JN); R: rows per wavefront, all of whose loads
+// are issued before the first is used (the kernel is a stream: bytes in flight are what counts).
+// zero_ptr/zero_n: flags that a later launch of the same call expects to find cleared.
+template <bool XF32, int JN, int R>
 __global__ __launch_bounds__(256) void layernorm_kernel(const void* __restrict__ xv, const uint16_t* __restrict__ gamma,
                                                         const uint16_t* __restrict__ beta, float eps,
-                                                        uint16_t* __restrict__ y, int M, int C) {
+                                                        uint16_t* __restrict__ y, int M, int C, int32_t* zero_ptr, int zero_n) {
+    if (blockIdx.x == 0)
+        for (int i = threadIdx.x; i < zero_n; i += 256) zero_ptr[i] = 0;
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= M) return;
+    const int row0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * R;
+    if (row0 >= M) return;
     const int nch = C >> 2;   // 4-element chunks per row
-    float v[LN_MAXJ][4];
+    float v[R][JN][4];
 #pragma unroll
-    for (int j = 0; j < LN_MAXJ; ++j) {
-        const int ch = lane + j * 64;
-        if (ch < nch) {
-            if (XF32) {
-                const float4 t = reinterpret_cast<const float4*>(static_cast<const float*>(xv) + (size_t)row * C)[ch];
-                v[j][0] = t.x; v[j][1] = t.y; v[j][2] = t.z; v[j][3] = t.w;
+    for (int r = 0; r < R; ++r) {
+        const int row = min(row0 + r, M - 1);   // rows past the end repeat the last one and are not stored
+#pragma unroll
+        for (int j = 0; j < JN; ++j) {
+            const int ch = lane + j * 64;
+            if (ch < nch) {
+                if (XF32) {
+                    const float4 t = reinterpret_cast<const float4*>(static_cast<const float*>(xv) + (size_t)row * C)[ch];
+                    v[r][j][0] = t.x; v[r][j][1] = t.y; v[r][j][2] = t.z; v[r][j][3] = t.w;
+                } else {
+                    const uint2 t = reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(xv) + (size_t)row * C)[ch];
+                    v[r][j][0] = bf16lo_to_f32(t.x); v[r][j][1] = bf16hi_to_f32(t.x);
+                    v[r][j][2] = bf16lo_to_f32(t.y); v[r][j][3] = bf16hi_to_f32(t.y);
+                }
             } else {
-                const uint2 t = reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(xv) + (size_t)row * C)[ch];
-                v[j][0] = bf16lo_to_f32(t.x); v[j][1] = bf16hi_to_f32(t.x);
-                v[j][2] = bf16lo_to_f32(t.y); v[j][3] = bf16hi_to_f32(t.y);
+                v[r][j][0] = v[r][j][1] = v[r][j][2] = v[r][j][3] = 0.f;
             }
-        } else {
-            v[j][0] = v[j][1] = v[j][2] = v[j][3] = 0.f;
         }
     }
-    // One pass over the registers for both moments, taken about the row's first element (a
-    // sample of the row, so the variance below loses no digits to a large common offset),
-    // and one reduction for the pair.
-    const float shift = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v[0][0])));
-    float s1 = 0.f, s2 = 0.f;
+    uint2 gg[JN], bb[JN];
 #pragma unroll
-    for (int j = 0; j < LN_MAXJ; ++j) {
+    for (int j = 0; j < JN; ++j) {
         const int ch = lane + j * 64;
-        if (ch < nch) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                v[j][e] -= shift;
-                s1 += v[j][e];
-                s2 += v[j][e] * v[j][e];
-            }
-        }
+        gg[j] = ch < nch ? reinterpret_cast<const uint2*>(gamma)[ch] : make_uint2(0, 0);
+        bb[j] = ch < nch ? reinterpret_cast<const uint2*>(beta)[ch] : make_uint2(0, 0);
     }
-    s1 = wave_sum(s1);
-    s2 = wave_sum(s2);
     const float inv_c = 1.0f / (float)C;
-    const float dmean = s1 * inv_c;                      // mean - shift
-    const float var = fmaxf(s2 * inv_c - dmean * dmean, 0.f);
-    const float rstd = rsqrtf(var + eps);
 #pragma unroll
-    for (int j = 0; j < LN_MAXJ; ++j)
+    for (int r = 0; r < R; ++r) {
+        // One pass over the registers for both moments, taken about the row's first element (a
+        // sample of the row, so the variance below loses no digits to a large common offset),
+        // and one reduction for the pair.
+        const float shift = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, v[r][0][0])));
+        float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[j][e] -= dmean;
+        for (int j = 0; j < JN; ++j) {
+            const int ch = lane + j * 64;
+            if (ch < nch) {
 #pragma unroll
-    for (int j = 0; j < LN_MAXJ; ++j) {
-        const int ch = lane + j * 64;
-        if (ch < nch) {
-            const uint2 gg = reinterpret_cast<const uint2*>(gamma)[ch];
-            const uint2 bb = reinterpret_cast<const uint2*>(beta)[ch];
-            const float o0 = v[j][0] * rstd * bf16lo_to_f32(gg.x) + bf16lo_to_f32(bb.x);
-            const float o1 = v[j][1] * rstd * bf16hi_to_f32(gg.x) + bf16hi_to_f32(bb.x);
-            const float o2 = v[j][2] * rstd * bf16lo_to_f32(gg.y) + bf16lo_to_f32(bb.y);
-            const float o3 = v[j][3] * rstd * bf16hi_to_f32(gg.y) + bf16hi_to_f32(bb.y);
-            uint2 o;
-            o.x = pack_bf16x2(o0, o1);
-            o.y = pack_bf16x2(o2, o3);
-            reinterpret_cast<uint2*>(y + (size_t)row * C)[ch] = o;
+                for (int e = 0; e < 4; ++e) {
+                    v[r][j][e] -= shift;
+                    s1 += v[r][j][e];
+                    s2 += v[r][j][e] * v[r][j][e];
+                }
+            }
+        }
+        s1 = wave_sum(s1);
+        s2 = wave_sum(s2);
+        const float dmean = s1 * inv_c;                      // mean - shift
+        const float var = fmaxf(s2 * inv_c - dmean * dmean, 0.f);
+        const float rstd = rsqrtf(var + eps);
+        if (row0 + r < M) {
+#pragma unroll
+            for (int j = 0; j < JN; ++j) {
+                const int ch = lane + j * 64;
+                if (ch < nch) {
+                    const float o0 = (v[r][j][0] - dmean) * rstd * bf16lo_to_f32(gg[j].x) + bf16lo_to_f32(bb[j].x);
+                    const float o1 = (v[r][j][1] - dmean) * rstd * bf16hi_to_f32(gg[j].x) + bf16hi_to_f32(bb[j].x);
+                    const float o2 = (v[r][j][2] - dmean) * rstd * bf16lo_to_f32(gg[j].y) + bf16lo_to_f32(bb[j].y);
+                    const float o3 = (v[r][j][3] - dmean) * rstd * bf16hi_to_f32(gg[j].y) + bf16hi_to_f32(bb[j].y);
+                    uint2 o;
+                    o.x = pack_bf16x2(o0, o1);
+                    o.y = pack_bf16x2(o2, o3);
+                    reinterpret_cast<uint2*>(y + (size_t)(row0 + r) * C)[ch] = o;
+                }
+            }
         }
     }
 }
 
+// rows per wavefront: whole-step timings favour one (more, smaller workgroups) over two or four
+constexpr int LN_ROWS = 1;
+template <bool XF32, int JN, int R>
+static void launch_ln(const void* x, const uint16_t* gamma, const uint16_t* beta, float eps, uint16_t* y, int M, int C,
+                      int32_t* zero_ptr, int zero_n, hipStream_t stream) {
+    hipLaunchKernelGGL((layernorm_kernel<XF32, JN, R>), dim3((M + 4 * R - 1) / (4 * R)), dim3(256), 0, stream, x, gamma, beta, eps, y, M, C,
+                       zero_ptr, zero_n);
+}
+
 int launch_layernorm(const void* x, int x_f32, const uint16_t* gamma, const uint16_t* beta, float eps,
-                     uint16_t* y, int M, int C, hipStream_t stream) {
+                     uint16_t* y, int M, int C, hipStream_t stream, int32_t* zero_ptr, int zero_n) {
     SD_REQUIRE(C % 4 == 0 && C > 0 && C <= 64 * 4 * LN_MAXJ, SD_EUNSUPPORTED, "layernorm: C=%d (need C %% 4 == 0, C <= %d)", C,
                64 * 4 * LN_MAXJ);
-    if (M <= 0) return SD_OK;
-    dim3 grid((M + 3) / 4), block(256);
-    if (x_f32) hipLaunchKernelGGL(layernorm_kernel<true>, grid, block, 0, stream, x, gamma, beta, eps, y, M, C);
-    else hipLaunchKernelGGL(layernorm_kernel<false>, grid, block, 0, stream, x, gamma, beta, eps, y, M, C);
+    if (M <= 0) return zero_n > 0 ? launch_clear_flags(zero_ptr, zero_n, stream) : SD_OK;
+    if (C <= 768) {          // SDXL's 320 and 640 channels: three chunks per lane
+        if (x_f32) launch_ln<true, 3, LN_ROWS>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+        else launch_ln<false, 3, LN_ROWS>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+    } else if (C <= 1280) {
+        if (x_f32) launch_ln<true, 5, 1>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+        else launch_ln<false, 5, 1>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+    } else {
+        if (x_f32) launch_ln<true, LN_MAXJ, 1>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+        else launch_ln<false, LN_MAXJ, 1>(x, gamma, beta, eps, y, M, C, zero_ptr, zero_n, stream);
+    }
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
