@@ -130,15 +130,18 @@ def main() -> int:
                 "attn_out": 2 * cfg.depth, "ff1": cfg.depth, "ff2": cfg.depth}
     M, C, T, Bn, F, r = cfg.M, cfg.C, cfg.T, cfg.Bn, cfg.F, cfg.r
     rl = r if cfg.lora_ff else 0
+    # every projection launch holds its down-projection tiles (x A^T), its base GEMM with the
+    # K segment extended by r, and nothing else; the q/k/v launch also holds the next
+    # cross-attention's text keys / values
+    def proj(m, k, n, rr):
+        return 2.0 * m * k * n + (2.0 * m * k * rr + 2.0 * m * rr * n if rr else 0.0)
     flop_per_launch = {
         "self_attention": 4.0 * Bn * T * T * C,
         "cross_attention": 4.0 * Bn * T * cfg.Tc * C,
-        # base + up-projection (K extended by r) of q, k, v, plus the next cross-attention's text
-        # keys / values, which ride in the same grouped launch
-        "qkv": 3 * (2.0 * M * C * C + 2.0 * M * r * C) + 2 * (2.0 * Bn * cfg.Tc * cfg.Dc * C + 2.0 * Bn * cfg.Tc * r * C),
-        "attn_out": 2.0 * M * C * C + 2.0 * M * r * C,
-        "ff1": 2.0 * M * C * 2 * F + 2.0 * M * rl * 2 * F,
-        "ff2": 2.0 * M * F * C + 2.0 * M * rl * C,
+        "qkv": 3 * proj(M, C, C, r) + 2 * proj(Bn * cfg.Tc, cfg.Dc, C, r),
+        "attn_out": proj(M, C, C, r),
+        "ff1": proj(M, C, 2 * F, rl),
+        "ff2": proj(M, F, C, rl),
     }
     B.timing_enable(K * max(per_step.values()) + 8)
     for _ in range(K):
