@@ -49,6 +49,7 @@ struct ProjOut {
     bool transposed;    // store y^T: y[n * ldy + m]
     int geglu_F;        // > 0: GEGLU epilogue, N == F
     float alpha;        // output scale applied to the accumulator before bias (0 means 1)
+    int res_f32;        // residual is fp32 although y is bf16 (with an fp32 y the residual always is)
 };
 
 static int check_proj(const sd_proj* p, const char* name, int K) {
@@ -100,7 +101,7 @@ static int push_main(GemmGroup& g, hipStream_t stream, const ProjCall& c, const 
     G.alpha = o.alpha != 0.f ? o.alpha : 1.0f;
     G.bias = p.bias;
     G.res = o.res; G.ldr = o.ldr;
-    G.y = o.y; G.ldy = o.ldy; G.y_f32 = o.y_f32;
+    G.y = o.y; G.ldy = o.ldy; G.y_f32 = o.y_f32; G.res_f32 = o.y_f32 || o.res_f32;
     G.geglu_F = o.geglu_F;
     G.K0 = c.K; G.K1 = r;
     if (!o.transposed) {
@@ -313,12 +314,16 @@ static bool carve_ff(Workspace& ws, FfWs& w, int M, int C, int F, int rmax) {
 }
 
 static int ff_sublayer(const void* x, void* y, int io_f32, const uint16_t* g, const uint16_t* b, float eps,
-                       const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream, DepFlags* dep = nullptr) {
+                       const sd_proj& p1, const sd_proj& p2, int M, int C, int F, const FfWs& w, hipStream_t stream, DepFlags* dep = nullptr,
+                       uint16_t* y_bf16 = nullptr) {
     int rc = layernorm(x, io_f32, g, b, eps, w.n, M, C, stream, dep);
     if (rc) return rc;
     ProjCall c1 = {w.n, C, M, C, F, &p1, w.t1, {w.g, F, 0, nullptr, 0, false, F}};
     if ((rc = run_projections(&c1, 1, stream, SD_TIMING_FF1, dep))) return rc;
+    // y_bf16: the sub-layer's output goes there, rounded once from the fp32 sum, instead of to y
+    // (the stack's last block: what follows reads bf16, and the fp32 stream is not needed again)
     ProjCall c2 = {w.g, F, M, F, C, &p2, w.t2, {y, C, io_f32, x, C, false, 0}};
+    if (y_bf16) c2.o = {y_bf16, C, 0, x, C, false, 0, 0.f, io_f32};
     return run_projections(&c2, 1, stream, SD_TIMING_FF2, dep);
 }
 
@@ -632,10 +637,13 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
             return rc;
         if ((rc = attn_sublayer(sw.h, sw.h, 1, ctx, Tc, Dc, b.ln2_g, b.ln2_b, 1e-5f, b.q2, b.k2, b.v2, b.o2, Bn, T, C, heads, sw.a, s, nullptr, true, &sw.dep)))
             return rc;
-        if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s, &sw.dep))) return rc;
+        // the last block hands its output to proj_out as bf16 directly
+        if ((rc = ff_sublayer(sw.h, sw.h, 1, b.ln3_g, b.ln3_b, 1e-5f, b.ff1, b.ff2, M, C, 4 * C, sw.f, s, &sw.dep,
+                              i == p->depth - 1 ? sw.g : nullptr)))
+            return rc;
     }
     // proj_out + input residual, bf16 out
-    if ((rc = launch_cvt_f32_to_bf16(sw.h, sw.g, (size_t)M * C, s))) return rc;
+    if (p->depth == 0 && (rc = launch_cvt_f32_to_bf16(sw.h, sw.g, (size_t)M * C, s))) return rc;
     ProjCall cout = {sw.g, C, M, C, C, &p->proj_out, sw.f.t1, {y, C, 0, x, C, false, 0}};
     return run_projections(&cout, 1, s, -1, &sw.dep);
 }

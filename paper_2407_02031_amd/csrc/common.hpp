@@ -113,13 +113,14 @@ struct GemmProblem {
     const uint16_t* p0; const uint16_t* q0;   // segment 0: P [Mp, K0], Q [Nq, K0]
     const uint16_t* p1; const uint16_t* q1;   // segment 1 (LoRA: P = scaled x A^T, Q = B), or null
     const uint16_t* bias;                      // per output column (or per row if bias_on_rows)
-    const void* res;                           // [Mp, N] of the output dtype, or null
+    const void* res;                           // [Mp, N], or null
     void* y;
     int64_t ldp0, ldq0, ldp1, ldq1, ldr, ldy;
     int32_t Mp, N;                             // output rows, output columns
     int32_t K0, K1;
     int32_t geglu_F;                           // > 0: Q has 2F rows (value, gate); N == F
-    int32_t y_f32;                             // output/residual dtype: 1 fp32, 0 bf16
+    int32_t y_f32;                             // output dtype: 1 fp32, 0 bf16
+    int32_t res_f32;                           // residual dtype (an fp32 stream may be added into a bf16 output)
     int32_t bias_on_rows;
     float alpha;
     int32_t tile_begin, tiles_m, tiles_n;      // filled by the launcher

@@ -348,7 +348,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
     // fp32 residual: fetch this lane's pieces of the whole wave tile now, so that the loads
     // fly during the last tile's MFMAs and the epilogue never waits piece by piece
     f32x4 rpre[RES32 ? MI : 1][RES32 ? NOUT / CB : 1][RES32 ? NPASS : 1];
-    const bool res_pre = RES32 && P.res && y_f32 && ld_ok;
+    const bool res_pre = RES32 && P.res && P.res_f32 && ld_ok;
     if (RES32 && res_pre) {
         const float* rp = static_cast<const float*>(P.res);
 #pragma unroll
@@ -431,6 +431,16 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
                     } else {
                         uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
                         const uint16_t* rp = static_cast<const uint16_t*>(P.res);
+                        if (P.res_f32 && rp) {      // fp32 residual stream into a bf16 output
+                            const float* rf = static_cast<const float*>(P.res);
+                            if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
+                            else if (vec_ok) val += *reinterpret_cast<const f32x4*>(rf + ri);
+                            else
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (q4 + e < N) val[e] += rf[ri + e];
+                            rp = nullptr;
+                        }
                         if (vec_ok) {
                             if (rp) {
                                 const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
@@ -545,7 +555,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     bool res32 = false;   // some problem adds an fp32 residual: take the kernel that prefetches it
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
-        if (P.res && P.y_f32 && P.Mp > 0 && P.N > 0) res32 = true;
+        if (P.res && P.res_f32 && P.Mp > 0 && P.N > 0) res32 = true;
         SD_REQUIRE((P.geglu_F > 0) == geglu || P.signal, SD_EINVAL, "gemm group mixes GEGLU and plain problems");
         SD_REQUIRE(P.Mp >= 0 && P.N >= 0 && P.K0 > 0 && P.K0 % 8 == 0 && P.K1 >= 0 && P.K1 % 8 == 0, SD_EINVAL,
                    "gemm problem %d: bad sizes M=%d N=%d K0=%d K1=%d", i, P.Mp, P.N, P.K0, P.K1);
