@@ -185,7 +185,7 @@ def main() -> int:
     mx = B.to_bf16(mp["x"])
     mproj = [(B.to_bf16(pr["W"]), [B.to_bf16(a) for a in pr["A"]], [B.to_bf16(b) for b in pr["B"]], pr["scales"]) for pr in mp["projs"]]
     my = torch.empty((mx.shape[0], mcfg.C), dtype=torch.bfloat16, device="cuda")
-    mws = torch.empty(mx.shape[0] * 64 * 2 + 256, dtype=torch.uint8, device="cuda")
+    mws = torch.empty(B.lib().sd_multi_lora_linear_workspace_bytes(mx.shape[0], max(mcfg.ranks)), dtype=torch.uint8, device="cuda")
 
     def mstep():
         for Wd, Ad, Bd, sc in mproj:

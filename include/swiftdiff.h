@@ -101,6 +101,11 @@ int32_t sd_version(void);
  * unless that protocol is broken, in which case outputs were wrong.  count: host.
  * Synchronises the device. */
 int sd_gemm_dep_timeouts(int64_t* count);
+/* Diagnostic switch for the same: on = 0 makes every later call run a projection as two
+ * launches (all down-projections, then all base GEMMs) instead of one; on = 1 (the default)
+ * restores the single launch.  Both give the same bits.  Returns the previous setting.
+ * Process-wide, not thread-safe against concurrent forward calls. */
+int32_t sd_set_projection_fusion(int32_t on);
 
 /* ---- instrumentation (off by default) --------------------------------------------------
  * Measurement support for the roofline figures: when enabled, the sub-layer and stack calls

@@ -77,6 +77,7 @@ def _load() -> C.CDLL:
         "sd_last_error": (C.c_char_p, []),
         "sd_version": (i32, []),
         "sd_gemm_dep_timeouts": (C.c_int, [P(i64)]),
+        "sd_set_projection_fusion": (i32, [i32]),
         "sd_timing_enable": (C.c_int, [i32]),
         "sd_timing_collect": (C.c_int, [i32, P(f32), i32, P(i32)]),
         "sd_timing_disable": (C.c_int, []),
@@ -124,7 +125,7 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32",
+EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_set_projection_fusion", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32",
            "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_workspace_bytes", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd", "sd_groupnorm_silu_fwd",
@@ -137,6 +138,10 @@ EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_timing_ena
 
 def lib() -> C.CDLL:
     return _lib
+
+
+def set_projection_fusion(on: bool) -> bool:
+    return bool(_lib.sd_set_projection_fusion(1 if on else 0))
 
 
 def gemm_dep_timeouts() -> int:

@@ -166,39 +166,58 @@ static int layernorm(const void* x, int x_f32, const uint16_t* g, const uint16_t
 // (by then they are long done, except in the first round of workgroups).  Without, or when the
 // projections do not fit one group, as two rounds of launches: every down-projection, then
 // every base GEMM.
+static bool g_fuse_projections = true;   // diagnostic switch, see sd_set_projection_fusion
+
 static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1, DepFlags* dep = nullptr) {
     GemmGroup g;
     memset(&g, 0, sizeof(g));
     int rc;
-    if (dep && dep->f[0]) {
-        int problems = 0, downs = 0;
-        size_t flags = 0;
+    auto problems_of = [](const ProjCall& c) { return c.M <= 0 ? 0 : (c.p->r > 0 ? 2 : 1); };
+    auto flags_of = [](const ProjCall& c) { return (c.M > 0 && c.p->r > 0) ? ((size_t)c.M + 63) / 64 : (size_t)0; };
+    bool fuse = g_fuse_projections && dep && dep->f[0];
+    if (fuse) {
+        bool any_down = false;
         for (int i = 0; i < n; ++i) {
-            if (calls[i].M <= 0) continue;
-            ++problems;
-            if (calls[i].p->r > 0) { ++problems; ++downs; flags += ((size_t)calls[i].M + 63) / 64; }
+            if (flags_of(calls[i]) > (size_t)dep->cap) fuse = false;   // one projection alone overflows the flags
+            if (flags_of(calls[i])) any_down = true;
         }
-        if (downs > 0 && problems <= GEMM_MAX_PROBLEMS && flags <= (size_t)dep->cap) {
-            if ((rc = dep->clear_now(stream))) return rc;
+        fuse = fuse && any_down;
+    }
+    if (fuse) {
+        // as many projections per launch as fit a group and the flags (projections are independent
+        // of each other, so any split is valid)
+        timing_mark(tag, 0, stream);
+        int i0 = 0;
+        while (i0 < n) {
+            int i1 = i0, problems = 0;
+            size_t flags = 0;
+            while (i1 < n && problems + problems_of(calls[i1]) <= GEMM_MAX_PROBLEMS && flags + flags_of(calls[i1]) <= (size_t)dep->cap) {
+                problems += problems_of(calls[i1]);
+                flags += flags_of(calls[i1]);
+                ++i1;
+            }
+            if (flags > 0 && (rc = dep->clear_now(stream))) return rc;
             int32_t* const base = dep->f[dep->turn];
             std::vector<int32_t*> slot(n, nullptr);
             size_t used = 0;
-            for (int i = 0; i < n; ++i) {
-                if (calls[i].M <= 0 || calls[i].p->r <= 0) continue;
+            for (int i = i0; i < i1; ++i) {
+                if (!flags_of(calls[i])) continue;
                 slot[i] = base + used;
-                used += ((size_t)calls[i].M + 63) / 64;
+                used += flags_of(calls[i]);
                 if ((rc = push_down(g, stream, calls[i], slot[i]))) return rc;
             }
-            for (int i = 0; i < n; ++i)
+            for (int i = i0; i < i1; ++i)
                 if (calls[i].M > 0 && (rc = push_main(g, stream, calls[i], slot[i]))) return rc;
-            dep->turn ^= 1;
-            g.zero_ptr = dep->f[dep->turn];
-            g.zero_n = dep->cap;
-            timing_mark(tag, 0, stream);
-            rc = flush(g, stream);
-            timing_mark(tag, 1, stream);
-            return rc;
+            if (flags > 0) {
+                dep->turn ^= 1;
+                g.zero_ptr = dep->f[dep->turn];
+                g.zero_n = dep->cap;
+            }
+            if ((rc = flush(g, stream))) return rc;
+            i0 = i1;
         }
+        timing_mark(tag, 1, stream);
+        return SD_OK;
     }
     for (int i = 0; i < n; ++i)
         if (calls[i].M > 0 && (rc = push_down(g, stream, calls[i]))) return rc;
@@ -340,6 +359,11 @@ using namespace sd;
 
 extern "C" const char* sd_last_error(void) { return g_err; }
 extern "C" int32_t sd_version(void) { return 1; }
+extern "C" int32_t sd_set_projection_fusion(int32_t on) {
+    const int32_t was = g_fuse_projections ? 1 : 0;
+    g_fuse_projections = on != 0;
+    return was;
+}
 extern "C" int sd_gemm_dep_timeouts(int64_t* count) {
     SD_REQUIRE(count, SD_EINVAL, "gemm_dep_timeouts: null count");
     long long v = 0;
@@ -653,7 +677,7 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
 // ---------------------------------------------------------------------------------------
 extern "C" size_t sd_multi_lora_linear_workspace_bytes(int32_t M, int32_t r_max) {
     if (M <= 0) return 256;
-    return round_up((size_t)M * (r_max > 0 ? r_max : 8) * 2, 256);
+    return round_up((size_t)M * (r_max > 0 ? r_max : 8) * 2, 256) + (r_max > 0 ? DepFlags::bytes_for(M) : 0);
 }
 
 extern "C" int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, const uint16_t* bias, const uint16_t* const* A_ptrs,
@@ -680,7 +704,12 @@ extern "C" int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, co
     SD_REQUIRE(ws && ws_bytes >= sd_multi_lora_linear_workspace_bytes(M, rmax), SD_EWORKSPACE, "multi_lora: workspace of %zu bytes, need %zu",
                ws_bytes, sd_multi_lora_linear_workspace_bytes(M, rmax));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    uint16_t* t = static_cast<uint16_t*>(ws);   // segment i's down-projection lives at t + offset_i * rmax
+    Workspace wsp(ws, ws_bytes);
+    uint16_t* t = (uint16_t*)wsp.take((size_t)M * (rmax > 0 ? rmax : 8) * 2);   // segment i's down-projection lives at t + offset_i * rmax
+    DepFlags dep;
+    if (rmax > 0) dep.carve(wsp, M);
+    SD_REQUIRE(wsp.ok(), SD_EWORKSPACE, "multi_lora: workspace too small");
+    dep.reset();
     std::vector<sd_proj> projs(nseg);
     std::vector<ProjCall> calls;
     for (int i = 0; i < nseg; ++i) {
@@ -692,5 +721,5 @@ extern "C" int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, co
         pr.r = a >= 0 ? ranks[a] : 0; pr.scale = a >= 0 ? scales[a] : 0.f;
         calls.push_back({x + (size_t)lo * K, K, rows, K, N, &pr, t + (size_t)lo * rmax, {y + (size_t)lo * N, N, 0, nullptr, 0, false, 0}});
     }
-    return run_projections(calls.data(), (int)calls.size(), s);
+    return run_projections(calls.data(), (int)calls.size(), s, -1, &dep);
 }

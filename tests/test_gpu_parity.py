@@ -513,6 +513,41 @@ def test_stack_graph_replay_matches_eager(B):
         assert torch.equal(again, y_eager)
 
 
+def test_projections_as_one_launch_or_two_give_the_same_bits(B):
+    """A projection runs as one launch (base-GEMM tiles wait for the down-projection tiles of the
+    same grid) or, with the diagnostic switch off, as two; the arithmetic is the same, so the
+    whole stack and a many-segment multi-LoRA batch must agree bit for bit."""
+    import torch
+    cfg = small_cfg(T=200, depth=2)
+    p = G.make_stack_inputs(cfg, seed=5)
+    sp = B.StackParams(p)
+    x, ctx = dev(p["x"], B), dev(p["ctx"], B)
+    # 20 segments of 3 adapters: more projections than one launch's group holds
+    mcfg = G.MultiLoraConfig(name="m", requests=20, T=70, C=128, ranks=(8, 16, 32), request_adapter=tuple(i % 3 for i in range(20)),
+                             std=0.08, x_std=1.0)
+    mp = G.make_multi_lora_inputs(mcfg, seed=3, n_proj=1, bias=True)
+    pr = mp["projs"][0]
+    offs = [70 * i for i in range(21)]
+    adp = [(-1 if i % 7 == 6 else i % 3) for i in range(20)]
+    margs = (dev(mp["x"], B), dev(pr["W"], B), dev(pr["b"], B), [dev(a, B) for a in pr["A"]], [dev(b, B) for b in pr["B"]],
+             [0.5, 1.0, 2.0], offs, adp)
+    mref = O.multi_lora_linear(mp["x"], pr["W"], pr["b"], pr["A"], pr["B"], [0.5, 1.0, 2.0], offs, adp)
+    outs = {}
+    try:
+        for on in (False, True):
+            B.set_projection_fusion(on)
+            y = B.spatial_transformer_fwd(x, ctx, sp, cfg.heads)
+            my = B.multi_lora_linear_fwd(*margs)
+            torch.cuda.synchronize()
+            outs[on] = (y.clone(), my.clone())
+    finally:
+        B.set_projection_fusion(True)
+    assert torch.equal(outs[False][0], outs[True][0])
+    assert torch.equal(outs[False][1], outs[True][1])
+    assert rel_err(host(outs[True][1]), mref) <= BF16_TOL
+    assert B.gemm_dep_timeouts() == 0
+
+
 def test_zz_no_tile_gave_up_waiting(B):
     """Runs last in this file: across everything above, no base-GEMM tile ran out of spins
     while waiting for a down-projection tile of its own launch."""
