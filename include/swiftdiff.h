@@ -102,9 +102,10 @@ int32_t sd_version(void);
  * Synchronises the device. */
 int sd_gemm_dep_timeouts(int64_t* count);
 /* Diagnostic switch for the same: on = 0 makes every later call run a projection as two
- * launches (all down-projections, then all base GEMMs) instead of one; on = 1 (the default)
- * restores the single launch.  Both give the same bits.  Returns the previous setting.
- * Process-wide, not thread-safe against concurrent forward calls. */
+ * launches (all down-projections, then all base GEMMs) instead of one, and merge the halves
+ * of cut attention tiles in a kernel of their own instead of inside the attention launch;
+ * on = 1 (the default) restores the single launches.  Both give the same bits.  Returns the
+ * previous setting.  Process-wide, not thread-safe against concurrent forward calls. */
 int32_t sd_set_projection_fusion(int32_t on);
 
 /* ---- instrumentation (off by default) --------------------------------------------------

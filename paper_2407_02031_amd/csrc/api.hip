@@ -133,21 +133,28 @@ struct DepFlags {
     int cap = 0;
     int turn = 0;
     bool pending = false;   // f[0] still has to be cleared: by the next LayerNorm launch, or by a launch of its own
+    // Behind the first array: counters of the attention launches that cut tiles in half (who
+    // arrived first), cleared with it; every launch leaves them at zero again.
+    static constexpr int ARRIVED = 1024;
+    int32_t* arrived = nullptr;
     static int cap_for(size_t rows) { return (int)(4 * ((rows + 63) / 64) + 64); }
-    static size_t bytes_for(size_t rows) { return round_up((size_t)cap_for(rows) * 4, 256) * 2; }
+    static size_t half_bytes(size_t rows) { return round_up((size_t)(cap_for(rows) + ARRIVED) * 4, 256); }
+    static size_t bytes_for(size_t rows) { return half_bytes(rows) * 2; }
     bool carve(Workspace& ws, size_t rows) {
         cap = cap_for(rows);
         char* b = (char*)ws.take(bytes_for(rows));
         f[0] = (int32_t*)b;
-        f[1] = b ? (int32_t*)(b + bytes_for(rows) / 2) : nullptr;
+        f[1] = b ? (int32_t*)(b + half_bytes(rows)) : nullptr;
+        arrived = b ? f[0] + cap : nullptr;
         turn = 0;
         return b != nullptr;
     }
     void reset() { turn = 0; pending = f[0] != nullptr; }
+    int clear_words() const { return cap + ARRIVED; }
     int clear_now(hipStream_t stream) {
         if (!pending) return SD_OK;
         pending = false;
-        return launch_clear_flags(f[0], cap, stream);
+        return launch_clear_flags(f[0], clear_words(), stream);
     }
 };
 
@@ -156,7 +163,7 @@ static int layernorm(const void* x, int x_f32, const uint16_t* g, const uint16_t
                      hipStream_t stream, DepFlags* dep) {
     if (dep && dep->pending && M > 0) {
         dep->pending = false;
-        return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream, dep->f[0], dep->cap);
+        return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream, dep->f[0], dep->clear_words());
     }
     return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream);
 }
@@ -167,6 +174,7 @@ static int layernorm(const void* x, int x_f32, const uint16_t* g, const uint16_t
 // projections do not fit one group, as two rounds of launches: every down-projection, then
 // every base GEMM.
 static bool g_fuse_projections = true;   // diagnostic switch, see sd_set_projection_fusion
+static bool g_fuse_attention_merge = true;
 
 static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int tag = -1, DepFlags* dep = nullptr) {
     GemmGroup g;
@@ -313,7 +321,10 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
     int cut = 0;
-    rc = launch_attention(w.q, C, kbuf, C, vtbuf, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, k_prescaled, w.scratch, w.scratch_bytes, &cut, stream);
+    // the counters were cleared by this call's first LayerNorm launch, at the latest by the one above
+    int32_t* const arrived = (dep && dep->arrived && !dep->pending && g_fuse_attention_merge) ? dep->arrived : nullptr;
+    rc = launch_attention(w.q, C, kbuf, C, vtbuf, (int64_t)Bn * Tkp, w.a, C, Bn, T, Tk, Tkp, heads, k_prescaled, w.scratch, w.scratch_bytes, &cut, stream,
+                          arrived, DepFlags::ARRIVED);
     timing_mark(atag, 1, stream);
     if (rc) return rc;
     if ((rc = launch_attention_merge(w.scratch, w.a, C, Bn, T, heads, k_prescaled, cut, stream))) return rc;
@@ -362,6 +373,7 @@ extern "C" int32_t sd_version(void) { return 1; }
 extern "C" int32_t sd_set_projection_fusion(int32_t on) {
     const int32_t was = g_fuse_projections ? 1 : 0;
     g_fuse_projections = on != 0;
+    g_fuse_attention_merge = on != 0;
     return was;
 }
 extern "C" int sd_gemm_dep_timeouts(int64_t* count) {

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
                                                         const uint16_t* __restrict__ vt, int64_t ldvt,
                                                         uint16_t* __restrict__ out, int64_t ldo,
                                                         int Tq, int Tk, int Tkp, int heads, int qtiles, float c,
-                                                        int nfull, int nsplit, float* __restrict__ parts) {
+                                                        int nfull, int nsplit, float* __restrict__ parts, int32_t* __restrict__ arrived) {
     static_assert(QB == 1, "one 32-query block per wavefront");
     constexpr int BQ = 4 * 32 * QB;
     __shared__ u32x4 ldsK[2][64 * 8];   // [key (permuted within 16)][8 chunks of 8 d], 2-deep ring
@@ -438,7 +438,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
     // ---- a whole tile is normalised and stored; half of a cut tile leaves its state behind
     if (part < 0) {
         store_queries(o[0], l[0], out, ldo, b, Tq, q0 + l32, head, hi);
-    } else {
+    } else if (!arrived) {
         float* pp = parts + ((size_t)(tile - nfull) * 2 + part) * PART_FLOATS + tid;
 #pragma unroll
         for (int db = 0; db < 2; ++db)
@@ -446,6 +446,46 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const uint16_t* __res
             for (int v = 0; v < 16; ++v) pp[(db * 16 + v) * 256] = o[0][db][v];
         pp[32 * 256] = m[0];
         pp[33 * 256] = l[0];
+    } else {
+        // Merge inside the launch: both halves leave their state (device-scope stores: the other
+        // half may run on another XCD), then count themselves in; the one that arrives second
+        // reads the first one's state and finishes the tile.  Nobody waits.  The counter is
+        // zero before the launch and the second arrival puts it back.
+        const int cut = tile - nfull;
+        float* pp = parts + ((size_t)cut * 2 + part) * PART_FLOATS + tid;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) __hip_atomic_store(pp + (db * 16 + v) * 256, o[0][db][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pp + 32 * 256, m[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(pp + 33 * 256, l[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // a device-scope store counts until it is visible at that scope
+        __syncthreads();                                    // ... for every wave of this half; LDS is free from here on
+        int32_t* const first = reinterpret_cast<int32_t*>(&ldsK[0][0]);
+        if (tid == 0) *first = __hip_atomic_fetch_add(arrived + cut, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*first == 1) {
+            if (tid == 0) __hip_atomic_store(arrived + cut, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float* po = parts + ((size_t)cut * 2 + (1 - part)) * PART_FLOATS + tid;
+            const float mo = __hip_atomic_load(po + 32 * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float lo = __hip_atomic_load(po + 33 * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // the halves' maxima are in score units, or already in exponent units when the keys were prescaled
+            const float cm = PRE ? 1.0f : c;
+            const float mm = fmaxf(m[0], mo);
+            const float fs = __builtin_amdgcn_exp2f((m[0] - mm) * cm), fo = __builtin_amdgcn_exp2f((mo - mm) * cm);
+            // same expression, operand for operand, whichever half arrives second: first half's term, then second's
+            const float f0 = part == 0 ? fs : fo, f1 = part == 0 ? fo : fs;
+#pragma unroll
+            for (int db = 0; db < 2; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float ov = __hip_atomic_load(po + (db * 16 + v) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    const float a0 = part == 0 ? o[0][db][v] : ov, a1 = part == 0 ? ov : o[0][db][v];
+                    o[0][db][v] = a0 * f0 + a1 * f1;
+                }
+            const float lsum = (part == 0 ? l[0] : lo) * f0 + (part == 0 ? lo : l[0]) * f1;
+            store_queries(o[0], lsum, out, ldo, b, Tq, q0 + l32, head, hi);
+        }
     }
 }
 
@@ -503,7 +543,7 @@ size_t attention_scratch_bytes(int Bn, int Tq, int Tk, int heads) {
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
                      int Bn, int Tq, int Tk, int Tkp, int heads, bool k_prescaled, void* scratch, size_t scratch_bytes, int* cut_tiles,
-                     hipStream_t stream) {
+                     hipStream_t stream, int32_t* arrived, int arrived_n) {
     SD_REQUIRE(q && k && vt && out, SD_EINVAL, "attention: null pointer");
     SD_REQUIRE(Tk >= 1 && Tkp >= Tk && Tkp % 8 == 0, SD_EINVAL, "attention: Tk=%d Tkp=%d", Tk, Tkp);
     SD_REQUIRE(ldq % 8 == 0 && ldk % 8 == 0 && ldvt % 8 == 0 && ldo % 4 == 0, SD_EINVAL, "attention: leading dimensions");
@@ -518,14 +558,15 @@ int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t 
     const size_t need = (size_t)nsplit * 2 * PART_FLOATS * sizeof(float);
     if (nsplit > 0 && !(scratch && scratch_bytes >= need && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0)) nsplit = 0;
     const int nfull = (int)tiles - nsplit;
+    if (nsplit > arrived_n) arrived = nullptr;   // not enough counters: the halves are merged by the second kernel
     if (k_prescaled)
         hipLaunchKernelGGL((attention_kernel<1, true>), dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out,
-                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
+                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch), arrived);
     else
         hipLaunchKernelGGL((attention_kernel<1, false>), dim3((unsigned)(nfull + 2 * nsplit)), dim3(256), 0, stream, q, ldq, k, ldk, vt, ldvt, out,
-                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch));
+                           ldo, Tq, Tk, Tkp, heads, qtiles, c, nfull, nsplit, static_cast<float*>(scratch), arrived);
     SD_HIP_CHECK(hipGetLastError());
-    *cut_tiles = nsplit;
+    *cut_tiles = arrived ? 0 : nsplit;
     return SD_OK;
 }
 

@@ -168,11 +168,13 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
 size_t groupnorm_partials_bytes(int Bn, int T, int groups);
 
 // scratch: attention_scratch_bytes(...) bytes, 16-byte aligned, for the launches that cut
-// some tiles' key range in half (without it every workgroup takes one whole tile)
+// some tiles' key range in half (without it every workgroup takes one whole tile).
+// arrived: arrived_n counters, zero before the launch and zero again after it; with them the
+// half that finishes second merges the two inside the launch and *cut_tiles comes back 0
 int launch_attention(const uint16_t* q, int64_t ldq, const uint16_t* k, int64_t ldk,
                      const uint16_t* vt, int64_t ldvt, uint16_t* out, int64_t ldo,
                      int Bn, int Tq, int Tk, int Tkp, int heads, bool k_prescaled, void* scratch, size_t scratch_bytes, int* cut_tiles,
-                     hipStream_t stream);
+                     hipStream_t stream, int32_t* arrived = nullptr, int arrived_n = 0);
 // second kernel of a launch that cut tiles (*cut_tiles > 0 above): merges the halves into `out`
 int launch_attention_merge(const void* scratch, uint16_t* out, int64_t ldo, int Bn, int Tq, int heads, bool k_prescaled, int cut_tiles,
                            hipStream_t stream);
