@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 # WRITE_SIZE runs of this file, each scaled by the same counter's reading on a pure copy of
 # known size (lora_unpatch): see profiles/lora_patch_hbm_traffic.txt
 PATCH_TRAFFIC_BYTES = 10.64e9   # FETCH_SIZE + WRITE_SIZE per patch launch, scaled (profiles/lora_patch_hbm_traffic.txt)
+# the same two counters for the kernels that can be the stack's dominant one (same file), bytes per launch
+STACK_TRAFFIC_BYTES = {"self_attention": 65.3e6, "ff1": 122.6e6}
 
 
 def stack_flops(cfg) -> float:
@@ -161,7 +163,8 @@ def main() -> int:
              "ff2": "gemm_kernel, feed-forward out-projection", "qkv": "gemm_kernel, grouped q/k/v^T projections",
              "attn_out": "gemm_kernel, attention output projection", "cross_attention": "attention_kernel, cross-attention"}
     roofline = {"kernel": names[dom], "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": STACK_TRAFFIC_BYTES.get(dom) if cfg is G.SDXL64 else None,
                 "avg_launch_ms": kernels[dom]["avg_launch_ms"], "launches_per_step": per_step[dom],
                 "share_of_step": kernels[dom]["share_of_step"],
                 "measured": "HIP events around every launch of this kernel in %d eager steps" % K}
