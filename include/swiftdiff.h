@@ -15,7 +15,12 @@
  *  - The library never allocates, frees or synchronises.  Scratch memory comes from the
  *    caller's workspace `ws` (device, 256-byte aligned) of at least the size the matching
  *    *_workspace_bytes query returns; all work is enqueued on `stream` (a hipStream_t).
- *  - Same inputs give bit-identical outputs run to run (no atomics in reductions).
+ *    Its contents on entry do not matter and are undefined afterwards.  A workspace belongs
+ *    to one call at a time: the kernels of a call signal each other through flags in it, so
+ *    two calls that may run concurrently (different streams, overlapping graph launches) need
+ *    a workspace each.
+ *  - Same inputs give bit-identical outputs run to run (atomics only count arrivals, they
+ *    never carry data or decide an order of summation).
  */
 #ifndef SWIFTDIFF_H
 #define SWIFTDIFF_H
