@@ -2,9 +2,12 @@
 //
 // Every projection of the transformer block is y = x W^T (+ bias) with an optional LoRA
 // term scale * (x A^T) B^T (Section 2, "Low-Rank Adaptation").  The down-projection
-// t = scale * x A^T is a first, small GEMM; the up-projection then rides in the base
-// GEMM's K loop: [x | t] [W | B]^T, i.e. a second K segment of length r.  Epilogues:
-// bias, exact-erf GEGLU (Section 4.3's fused GEGLU), residual add, bf16 or fp32 store.
+// t = scale * x A^T is a small GEMM of its own; the up-projection then rides in the base
+// GEMM's K loop: [x | t] [W | B]^T, i.e. a second K segment of length r.  Both run in one
+// launch: the down-projection's tiles come first in the grid and raise a flag per row block,
+// and a base-GEMM tile looks at its flag only when it reaches the second K segment.
+// Epilogues: bias, exact-erf GEGLU (Section 4.3's fused GEGLU), residual add, bf16 or fp32
+// store.
 //
 // Tiling: BM x BN output tile per workgroup, BK = 64, WGM x WGN wavefronts, each owning
 // (BM/WGM) x (BN/WGN) as 32x32x16 bf16 MFMA tiles with fp32 accumulators.
