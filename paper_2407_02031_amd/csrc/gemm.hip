@@ -553,7 +553,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     bool geglu = false;   // a GEGLU group: GEGLU problems plus, possibly, the plain down-projections they wait for
     for (int i = 0; i < g.n; ++i) geglu = geglu || g.p[i].geglu_F > 0;
     bool guard = false;
-    int maxN = 0;
+    int maxN = 0, maxK = 0;
     long t128 = 0;        // workgroup tiles at 128x128
     bool res32 = false;   // some problem adds an fp32 residual: take the kernel that prefetches it
     for (int i = 0; i < g.n; ++i) {
@@ -579,6 +579,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (P.Mp == 0 || P.N == 0) continue;
         if ((P.K0 & 63) || (P.K1 & 63)) guard = true;
         if (P.N > maxN) maxN = P.N;
+        if (P.K0 > maxK) maxK = P.K0;
         t128 += (long)((P.Mp + 127) / 128) * ((P.N + 127) / 128);
     }
     // drop empty problems
@@ -596,7 +597,9 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // of 32x64, two workgroups per CU.  Down-projections (N = rank <= 64): 64x64 tiles, 5-stage
     // ring.
     if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false, false>(g, guard, stream);
-    if (t128 < 1024) {
+    // ... except long-K launches (the feed-forward out-projection, K = 4C) that still give every CU
+    // a 128x128 tile: over 40 k-steps the operand bytes per FLOP decide, not the ramps
+    if (t128 < 1024 && !(maxK >= 2048 && t128 >= 256)) {
         if (geglu) return launch_cfg<64, 128, 64, 2, 2, 2, true, false>(g, guard, stream);
         if (res32) return launch_cfg<64, 128, 64, 2, 2, 2, false, true>(g, guard, stream);
         return launch_cfg<64, 128, 64, 2, 2, 2, false, false>(g, guard, stream);
