@@ -96,6 +96,24 @@ def test_lora_linear_same_workspace_new_inputs(B):
     assert B.gemm_dep_timeouts() == 0
 
 
+def test_lora_linear_random_shapes(B):
+    """Seeded sweep over ragged shapes and ranks (rank > 64: two column tiles of down-projection
+    per row block, so a base tile waits for a count of 2; rank not a multiple of 64; one-row and
+    one-tile problems; more row blocks than CUs) through the single-launch projection."""
+    r = rng(2024)
+    shapes = [(1, 64, 8, 8), (63, 72, 40, 128), (64, 64, 64, 64), (65, 136, 264, 72), (129, 200, 136, 128),
+              (700, 640, 640, 96), (2100, 320, 136, 24), (20000, 64, 136, 8), (333, 1288, 72, 200)]
+    for _ in range(6):
+        shapes.append((int(r.integers(1, 900)), 8 * int(r.integers(1, 60)), 8 * int(r.integers(1, 60)), 8 * int(r.integers(1, 20))))
+    for (M, K, N, rank) in shapes:
+        p = mkproj(r, N, K, rank, bias=True, scale=0.7)
+        x = G.bf16_round(r.standard_normal((M, K)).astype(np.float32))
+        ref = O.lora_linear(x, p["W"], p["b"], p["A"], p["B"], p["scale"])
+        y = B.lora_linear_fwd(dev(x, B), B.Proj.from_numpy(p))
+        assert rel_err(host(y), ref) <= BF16_TOL, (M, K, N, rank)
+    assert B.gemm_dep_timeouts() == 0
+
+
 def test_lora_linear_layernorm_residual_fp32(B):
     import torch
     r = rng(7)
