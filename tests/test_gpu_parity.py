@@ -262,6 +262,36 @@ def test_attn_block_matches_oracle(B, cross, io):
         assert rel_err(got, ref) <= BF16_TOL
 
 
+@pytest.mark.parametrize("Bn,T,Tc,C,heads,rank", [(1, 1, 1, 64, 1, 8), (3, 70, 5, 64, 1, 16), (2, 129, 100, 128, 2, 72),
+                                                   (1, 600, 77, 192, 3, 128), (2, 257, 130, 128, 2, 8)])
+def test_attn_block_ragged_sizes(B, Bn, T, Tc, C, heads, rank):
+    """Self- and cross-attention sub-layers at ragged token counts, including ranks above 64 and
+    context lengths that are not multiples of 8: the v^T projection is a transposed problem whose
+    tiles wait for the down-projection row blocks that cover their token columns."""
+    import torch
+    # alpha fixed: the adapter's share of q and k, and with it the score scale, does not grow with the rank
+    cfg = small_cfg(Bn=Bn, T=T, Tc=Tc, C=C, heads=heads, r=rank, alpha=8.0, Dc=72)
+    p = G.make_stack_inputs(cfg, seed=T + Tc)
+    blk = p["blocks"][0]
+    h = rng(T).standard_normal(p["x"].shape).astype(np.float32)
+    for cross in (False, True):
+        names = ("q2", "k2", "v2", "o2", "ln2_g", "ln2_b") if cross else ("q1", "k1", "v1", "o1", "ln1_g", "ln1_b")
+        pq, pk, pv, po, g, b = (blk[n] for n in names)
+        ctx = p["ctx"] if cross else None
+        ref = O.attn_sublayer(h, ctx, g, b, pq, pk, pv, po, cfg.heads)
+        args = (torch.from_numpy(h).cuda(), dev(ctx, B) if cross else None, dev(g, B), dev(b, B), B.Proj.from_numpy(pq),
+                B.Proj.from_numpy(pk), B.Proj.from_numpy(pv), B.Proj.from_numpy(po), cfg.heads)
+        y = B.attn_block_fwd(*args)
+        assert rel_err(host(y) - h, ref - h) <= BF16_TOL, (cross,)
+        try:        # the same call as two launches per projection: same bits
+            B.set_projection_fusion(False)
+            y2 = B.attn_block_fwd(*args)
+        finally:
+            B.set_projection_fusion(True)
+        assert torch.equal(y, y2), (cross,)
+    assert B.gemm_dep_timeouts() == 0
+
+
 def test_ff_block_matches_oracle(B):
     import torch
     cfg = small_cfg(T=150, C=192, heads=3)
