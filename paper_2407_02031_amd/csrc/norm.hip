@@ -162,45 +162,48 @@ int launch_cvt_f32_to_bf16(const float* x, uint16_t* y, size_t n, hipStream_t st
 }
 
 // ---------------------------------------------------------------------------------------
-// GroupNorm, token-major [Bn, T, C].  Pass 1: per (sample, token chunk, group) sums of
+// GroupNorm, token-major [Bn, T, C].  Pass 1: per (sample, chunk of 64 tokens, group) sums of
 // (x - shift) and (x - shift)^2 with shift = the group's first element in the sample
 // (shifted-data variance: no catastrophic cancellation for data with a large mean).
-// Pass 2: combine the chunk partials in a fixed order and normalise.
+// Pass 2: every workgroup combines the chunk partials of its sample in a fixed order (a few
+// KB through LDS, so there is no finalize launch in between) and normalises its tokens.
 // Thread t of a block owns channel pair (2t, 2t+1); groups hold an even number of channels.
 // ---------------------------------------------------------------------------------------
-constexpr int GN_TCHUNK = 8;    // tokens per block: many small blocks, every load of a thread in flight at once
+constexpr int GN_TCHUNK = 8;    // tokens per apply block and per inner step of the partial pass: every load of a thread in flight at once
+constexpr int GN_PCHUNK_MIN = 32;    // tokens per partial-sum block ...
+constexpr int GN_MAX_PCHUNKS = 128;  // ... more for long samples, so that a sample never has more blocks than this
 
 __global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* __restrict__ partials,
-                                         int T, int C, int groups, int nchunks) {
+                                         int T, int C, int groups, int nchunks, int pchunk) {
     extern __shared__ float sh[];   // [C/2][2]
     const int b = blockIdx.y, chunk = blockIdx.x;
     const int cp = threadIdx.x;
     const int cpg = C / groups;
     const int npairs = C >> 1;
     const uint16_t* xb = x + (size_t)b * T * C;
-    const int t0 = chunk * GN_TCHUNK;
-    const int t1 = min(T, t0 + GN_TCHUNK);
+    const int t0 = chunk * pchunk;
+    const int t1 = min(T, t0 + pchunk);
     float s1 = 0.f, s2 = 0.f;
     if (cp < npairs) {
         const int g = (2 * cp) / cpg;
         const float shift = bf16_to_f32(xb[g * cpg]);
-        if (t1 - t0 == GN_TCHUNK) {
+        int t = t0;
+        for (; t + GN_TCHUNK <= t1; t += GN_TCHUNK) {
             uint32_t pr[GN_TCHUNK];
 #pragma unroll
-            for (int i = 0; i < GN_TCHUNK; ++i) pr[i] = reinterpret_cast<const uint32_t*>(xb + (size_t)(t0 + i) * C)[cp];
+            for (int i = 0; i < GN_TCHUNK; ++i) pr[i] = reinterpret_cast<const uint32_t*>(xb + (size_t)(t + i) * C)[cp];
 #pragma unroll
             for (int i = 0; i < GN_TCHUNK; ++i) {
                 const float a = bf16lo_to_f32(pr[i]) - shift, c = bf16hi_to_f32(pr[i]) - shift;
                 s1 += a + c;
                 s2 += a * a + c * c;
             }
-        } else {
-            for (int t = t0; t < t1; ++t) {
-                const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
-                const float a = bf16lo_to_f32(pr) - shift, c = bf16hi_to_f32(pr) - shift;
-                s1 += a + c;
-                s2 += a * a + c * c;
-            }
+        }
+        for (; t < t1; ++t) {
+            const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
+            const float a = bf16lo_to_f32(pr) - shift, c = bf16hi_to_f32(pr) - shift;
+            s1 += a + c;
+            s2 += a * a + c * c;
         }
         sh[2 * cp] = s1;
         sh[2 * cp + 1] = s2;
@@ -216,44 +219,43 @@ __global__ void groupnorm_partial_kernel(const uint16_t* __restrict__ x, float* 
     }
 }
 
-// One wavefront per (sample, group): fixed-order sum of the chunk partials -> (mean, rstd).
-__global__ __launch_bounds__(64) void groupnorm_finalize_kernel(const uint16_t* __restrict__ x, const float* __restrict__ partials,
-                                                               float* __restrict__ stats, int T, int C, int groups, int nchunks, float eps) {
-    const int b = blockIdx.x / groups, g = blockIdx.x % groups;
-    const int lane = threadIdx.x;
-    const int cpg = C / groups;
-    float a1 = 0.f, a2 = 0.f;
-    for (int c = lane; c < nchunks; c += 64) {
-        const float* p = partials + (((size_t)b * nchunks + c) * groups + g) * 2;
-        a1 += p[0];
-        a2 += p[1];
-    }
-    a1 = wave_sum(a1);
-    a2 = wave_sum(a2);
-    if (lane == 0) {
-        const float n = (float)T * (float)cpg;
-        const float m1 = a1 / n;
-        const float var = fmaxf(a2 / n - m1 * m1, 0.f);
-        stats[2 * blockIdx.x] = bf16_to_f32(x[(size_t)b * T * C + g * cpg]) + m1;
-        stats[2 * blockIdx.x + 1] = rsqrtf(var + eps);
-    }
-}
-
 // SILU: y = n * sigmoid(n) on the normalised value, the GroupNorm + SiLU pair of the base model's
 // ResNet blocks as one operator (Section 4.3, "Kernel-level optimizations")
 template <bool SILU>
 __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                        const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ beta,
-                                       const float* __restrict__ stats, int T, int C, int groups) {
+                                       const float* __restrict__ partials, int T, int C, int groups, int nchunks, float eps) {
+    extern __shared__ float sh[];   // [nchunks * groups][2] partials of this sample, then [groups][2] (mean, rstd)
     const int b = blockIdx.y, chunk = blockIdx.x;
     const int cp = threadIdx.x;
     const int cpg = C / groups;
     const int npairs = C >> 1;
-    if (cp >= npairs) return;
     const uint16_t* xb = x + (size_t)b * T * C;
     uint16_t* yb = y + (size_t)b * T * C;
+    // ---- statistics of the sample's groups: chunk partials summed in chunk order
+    {
+        const int np = nchunks * groups;
+        const float2* src = reinterpret_cast<const float2*>(partials) + (size_t)b * np;
+        float2* dst = reinterpret_cast<float2*>(sh);
+        for (int i = cp; i < np; i += blockDim.x) dst[i] = src[i];
+        __syncthreads();
+        float mean = 0.f, rstd = 0.f;
+        if (cp < groups) {
+            float a1 = 0.f, a2 = 0.f;
+            for (int c = 0; c < nchunks; ++c) { a1 += dst[c * groups + cp].x; a2 += dst[c * groups + cp].y; }
+            const float n = (float)T * (float)cpg;
+            const float m1 = a1 / n;
+            const float var = fmaxf(a2 / n - m1 * m1, 0.f);
+            mean = bf16_to_f32(xb[cp * cpg]) + m1;
+            rstd = rsqrtf(var + eps);
+        }
+        __syncthreads();
+        if (cp < groups) { sh[2 * cp] = mean; sh[2 * cp + 1] = rstd; }
+        __syncthreads();
+    }
+    if (cp >= npairs) return;
     const int g = (2 * cp) / cpg;
-    const float mean = stats[2 * (b * groups + g)], rstd = stats[2 * (b * groups + g) + 1];
+    const float mean = sh[2 * g], rstd = sh[2 * g + 1];
     const uint32_t gg = reinterpret_cast<const uint32_t*>(gamma)[cp];
     const uint32_t bb = reinterpret_cast<const uint32_t*>(beta)[cp];
     const float g0 = bf16lo_to_f32(gg) * rstd, g1 = bf16hi_to_f32(gg) * rstd;
@@ -273,9 +275,16 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
     }
 }
 
+// tokens per partial-sum block for samples of T tokens
+static int groupnorm_pchunk(int T) {
+    int p = (T + GN_MAX_PCHUNKS - 1) / GN_MAX_PCHUNKS;
+    p = (p + GN_TCHUNK - 1) / GN_TCHUNK * GN_TCHUNK;
+    return p < GN_PCHUNK_MIN ? GN_PCHUNK_MIN : p;
+}
+
 size_t groupnorm_partials_bytes(int Bn, int T, int groups) {
-    const size_t nchunks = (size_t)(T + GN_TCHUNK - 1) / GN_TCHUNK;
-    return round_up((size_t)Bn * nchunks * groups * 2 * sizeof(float), 256) + (size_t)Bn * groups * 2 * sizeof(float);
+    (void)T;
+    return round_up((size_t)Bn * GN_MAX_PCHUNKS * groups * 2 * sizeof(float), 256);
 }
 
 int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
@@ -284,18 +293,20 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
                "groupnorm: C=%d groups=%d (need an even number of channels per group)", C, groups);
     SD_REQUIRE(C <= 2048, SD_EUNSUPPORTED, "groupnorm: C=%d > 2048", C);
     if (Bn <= 0 || T <= 0) return SD_OK;
-    const int nchunks = (T + GN_TCHUNK - 1) / GN_TCHUNK;
+    const int pchunk = groupnorm_pchunk(T);
+    const int nchunks = (T + pchunk - 1) / pchunk;
+    // the apply pass keeps one sample's chunk partials in LDS
+    const size_t stats_lds = ((size_t)nchunks * groups + groups) * 2 * sizeof(float);
+    SD_REQUIRE(nchunks <= GN_MAX_PCHUNKS && stats_lds <= 64 * 1024, SD_EUNSUPPORTED, "groupnorm: T=%d groups=%d exceed the statistics buffer (%zu bytes of LDS)", T,
+               groups, stats_lds);
     int threads = ((C / 2 + 63) / 64) * 64;
     if (threads < 64) threads = 64;
     if (threads < groups) threads = ((groups + 63) / 64) * 64;
-    dim3 grid(nchunks, Bn);
-    hipLaunchKernelGGL(groupnorm_partial_kernel, grid, dim3(threads), (size_t)C * sizeof(float), stream, x, partials, T, C, groups, nchunks);
+    hipLaunchKernelGGL(groupnorm_partial_kernel, dim3(nchunks, Bn), dim3(threads), (size_t)C * sizeof(float), stream, x, partials, T, C, groups, nchunks, pchunk);
     SD_HIP_CHECK(hipGetLastError());
-    float* stats = partials + round_up((size_t)Bn * nchunks * groups * 2 * sizeof(float), 256) / sizeof(float);
-    hipLaunchKernelGGL(groupnorm_finalize_kernel, dim3(Bn * groups), dim3(64), 0, stream, x, partials, stats, T, C, groups, nchunks, eps);
-    SD_HIP_CHECK(hipGetLastError());
-    if (silu) hipLaunchKernelGGL(groupnorm_apply_kernel<true>, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
-    else hipLaunchKernelGGL(groupnorm_apply_kernel<false>, grid, dim3(threads), 0, stream, x, y, gamma, beta, stats, T, C, groups);
+    const dim3 grid((T + GN_TCHUNK - 1) / GN_TCHUNK, Bn);
+    if (silu) hipLaunchKernelGGL(groupnorm_apply_kernel<true>, grid, dim3(threads), stats_lds, stream, x, y, gamma, beta, partials, T, C, groups, nchunks, eps);
+    else hipLaunchKernelGGL(groupnorm_apply_kernel<false>, grid, dim3(threads), stats_lds, stream, x, y, gamma, beta, partials, T, C, groups, nchunks, eps);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
