@@ -225,13 +225,20 @@ template <bool SILU>
 __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y,
                                        const uint16_t* __restrict__ gamma, const uint16_t* __restrict__ beta,
                                        const float* __restrict__ partials, int T, int C, int groups, int nchunks, float eps) {
-    extern __shared__ float sh[];   // [nchunks * groups][2] partials of this sample, then [groups][2] (mean, rstd)
+    extern __shared__ float sh[];   // [nchunks * groups][2] partials of this sample + [8 * groups][2] run sums, then [groups][2] (mean, rstd)
     const int b = blockIdx.y, chunk = blockIdx.x;
     const int cp = threadIdx.x;
     const int cpg = C / groups;
     const int npairs = C >> 1;
     const uint16_t* xb = x + (size_t)b * T * C;
     uint16_t* yb = y + (size_t)b * T * C;
+    // this thread's inputs first: they are in flight while the statistics are put together
+    const int t0 = chunk * GN_TCHUNK;
+    const int t1 = min(T, t0 + GN_TCHUNK);
+    uint32_t pr[GN_TCHUNK];
+#pragma unroll
+    for (int i = 0; i < GN_TCHUNK; ++i)
+        pr[i] = (cp < npairs && t0 + i < t1) ? reinterpret_cast<const uint32_t*>(xb + (size_t)(t0 + i) * C)[cp] : 0u;
     // ---- statistics of the sample's groups: chunk partials summed in chunk order
     {
         const int np = nchunks * groups;
@@ -239,10 +246,22 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
         float2* dst = reinterpret_cast<float2*>(sh);
         for (int i = cp; i < np; i += blockDim.x) dst[i] = src[i];
         __syncthreads();
+        // group g's chunks are summed in `split` contiguous runs by `split` threads, and the runs
+        // then in run order: a fixed order for a given shape, and no long serial chain
+        const int split = min(8, (int)blockDim.x / groups);
+        const int run = (nchunks + split - 1) / split;
+        float2* sub = dst + np;   // [split][groups]
+        if (cp < split * groups) {
+            const int g = cp % groups, part = cp / groups;
+            float a1 = 0.f, a2 = 0.f;
+            for (int c = part * run; c < min(nchunks, (part + 1) * run); ++c) { a1 += dst[c * groups + g].x; a2 += dst[c * groups + g].y; }
+            sub[part * groups + g] = make_float2(a1, a2);
+        }
+        __syncthreads();
         float mean = 0.f, rstd = 0.f;
         if (cp < groups) {
             float a1 = 0.f, a2 = 0.f;
-            for (int c = 0; c < nchunks; ++c) { a1 += dst[c * groups + cp].x; a2 += dst[c * groups + cp].y; }
+            for (int p = 0; p < split; ++p) { a1 += sub[p * groups + cp].x; a2 += sub[p * groups + cp].y; }
             const float n = (float)T * (float)cpg;
             const float m1 = a1 / n;
             const float var = fmaxf(a2 / n - m1 * m1, 0.f);
@@ -260,18 +279,16 @@ __global__ void groupnorm_apply_kernel(const uint16_t* __restrict__ x, uint16_t*
     const uint32_t bb = reinterpret_cast<const uint32_t*>(beta)[cp];
     const float g0 = bf16lo_to_f32(gg) * rstd, g1 = bf16hi_to_f32(gg) * rstd;
     const float b0 = bf16lo_to_f32(bb), b1 = bf16hi_to_f32(bb);
-    const int t0 = chunk * GN_TCHUNK;
-    const int t1 = min(T, t0 + GN_TCHUNK);
-#pragma unroll 8
-    for (int t = t0; t < t1; ++t) {
-        const uint32_t pr = reinterpret_cast<const uint32_t*>(xb + (size_t)t * C)[cp];
-        float o0 = (bf16lo_to_f32(pr) - mean) * g0 + b0;
-        float o1 = (bf16hi_to_f32(pr) - mean) * g1 + b1;
+#pragma unroll
+    for (int i = 0; i < GN_TCHUNK; ++i) {
+        if (t0 + i >= t1) break;
+        float o0 = (bf16lo_to_f32(pr[i]) - mean) * g0 + b0;
+        float o1 = (bf16hi_to_f32(pr[i]) - mean) * g1 + b1;
         if (SILU) {
             o0 = o0 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * o0));
             o1 = o1 * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * o1));
         }
-        reinterpret_cast<uint32_t*>(yb + (size_t)t * C)[cp] = pack_bf16x2(o0, o1);
+        reinterpret_cast<uint32_t*>(yb + (size_t)(t0 + i) * C)[cp] = pack_bf16x2(o0, o1);
     }
 }
 
@@ -296,7 +313,7 @@ int launch_groupnorm(const uint16_t* x, uint16_t* y, const uint16_t* gamma, cons
     const int pchunk = groupnorm_pchunk(T);
     const int nchunks = (T + pchunk - 1) / pchunk;
     // the apply pass keeps one sample's chunk partials in LDS
-    const size_t stats_lds = ((size_t)nchunks * groups + groups) * 2 * sizeof(float);
+    const size_t stats_lds = ((size_t)nchunks * groups + 8 * groups) * 2 * sizeof(float);
     SD_REQUIRE(nchunks <= GN_MAX_PCHUNKS && stats_lds <= 64 * 1024, SD_EUNSUPPORTED, "groupnorm: T=%d groups=%d exceed the statistics buffer (%zu bytes of LDS)", T,
                groups, stats_lds);
     int threads = ((C / 2 + 63) / 64) * 64;
