@@ -503,8 +503,8 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
             tile = lead + (r & 7) * (rest >> 3) + (r >> 3);
         }
     }
-    if (blockIdx.x == gridDim.x - 1)   // flags of the next dependent launch: nothing reads them before this kernel ends
-        for (int i = threadIdx.x; i < g.zero_n; i += 64 * NW) g.zero_ptr[i] = 0;
+    // flags of the next dependent launch, a few words per workgroup: nothing reads them before this kernel ends
+    for (int i = blockIdx.x * (64 * NW) + threadIdx.x; i < g.zero_n; i += gridDim.x * (64 * NW)) g.zero_ptr[i] = 0;
     // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
     // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
     // problem pay a second round.
