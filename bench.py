@@ -340,12 +340,24 @@ def main() -> int:
     cc = float(np.median(time_events(lambda: B.ceiling_copy_f32(csrc, cdst), 5)))
     mfma_ceiling = cfl[0] / (cm * 1e-3) / 1e12
     copy_ceiling = 8.0 * csrc.numel() / (cc * 1e-3) / 1e9
+    del csrc, cdst
+    # the same copy at the patch sweep's own footprint (3.3 GB each way): the 256 MB last-level
+    # cache no longer helps, and this is the rate the patch kernels are up against
+    big = 830668800
+    csrc = torch.empty(big, device="cuda").normal_()
+    cdst = torch.empty_like(csrc)
+    B.ceiling_copy_f32(csrc, cdst)
+    cb = float(np.median(time_events(lambda: B.ceiling_copy_f32(csrc, cdst), 5)))
+    copy_large = 8.0 * big / (cb * 1e-3) / 1e9
     out["ceilings"] = {"mfma_bf16_tflops": round(mfma_ceiling, 1), "copy_f32_gbs": round(copy_ceiling, 1),
+                       "copy_f32_gbs_at_patch_footprint": round(copy_large, 1),
                        "value_frac_of_mfma_ceiling": round(tflops / mfma_ceiling, 4),
                        "dominant_kernel_frac_of_mfma_ceiling": round(kernels[dom]["tflops"] / mfma_ceiling, 4)}
     if "patch" in out:
         out["ceilings"]["patch_frac_of_copy_ceiling"] = round(out["patch"]["patch_gbs"] / copy_ceiling, 4)
         out["ceilings"]["unpatch_frac_of_copy_ceiling"] = round(out["patch"]["unpatch_gbs"] / copy_ceiling, 4)
+        out["ceilings"]["patch_frac_of_copy_at_patch_footprint"] = round(out["patch"]["patch_gbs"] / copy_large, 4)
+        out["ceilings"]["unpatch_frac_of_copy_at_patch_footprint"] = round(out["patch"]["unpatch_gbs"] / copy_large, 4)
     del csrc, cdst, cout
 
     # --------------------------------------------------------------------- CPU baseline
