@@ -159,19 +159,25 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_kernel(const PatchPl
         for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
     if (full) {
-        // W tile first: these loads stay in flight under the MFMA loop
         float4 w[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             w[v] = NT_LOAD4(W + (size_t)row * in + col);
         }
+        // the undo record needs nothing but W: it goes out as one burst of stores before the
+        // rank-r product, whose MFMAs then run under those stores (a little faster than with the
+        // undo and result stores interleaved afterwards)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            NT_STORE4(U + (size_t)row * in + col, w[v]);
+        }
         delta_full(A, B, r, in, r0, col, l32, hi, acc);
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             const size_t idx = (size_t)row * in + col;
-            NT_STORE4(U + idx, w[v]);
             float4 o;
             o.x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
             o.y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
