@@ -242,6 +242,12 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const P
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             w[v] = NT_LOAD4(W + (size_t)row * in + col);
         }
+        // W's old bits go out first, as one burst of stores, before any adapter's product
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
+            NT_STORE4(U + (size_t)row * in + col, w[v]);
+        }
 #pragma unroll 1
         for (int a = 0; a < na; ++a) {
 #pragma unroll
@@ -250,13 +256,6 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const P
                 for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
             delta_full(E.d.A[a], E.d.B[a], E.d.r[a], in, r0, col, l32, hi, acc);
             const float scale = E.d.scale[a];
-            if (a == 0) {   // W's old bits go out as soon as they have arrived
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
-                    NT_STORE4(U + (size_t)row * in + col, w[v]);
-                }
-            }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 w[v].x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
