@@ -124,3 +124,11 @@ def test_forward_calls_reject_bad_arguments_before_touching_the_device(B):
     sa = (C.c_int32 * 1)(-1)
     assert L.sd_multi_lora_linear_fwd(0x1000, 0x2000, None, None, None, None, None, so, sa, 1, 0, 0x3000, 8, 8, 8, 0x4000, 1 << 20, None) == -1
     assert b"cover" in L.sd_last_error()
+
+
+def test_projection_fusion_switch_is_host_state(B):
+    L = B.lib()
+    assert L.sd_set_projection_fusion(0) == 1      # on by default; returns the previous setting
+    assert L.sd_set_projection_fusion(1) == 0
+    assert L.sd_set_projection_fusion(1) == 1
+    assert L.sd_gemm_dep_timeouts(None) == -1       # null count is rejected before touching the device
