@@ -297,6 +297,23 @@ def cfg_combine(eps_uncond, eps_cond, guidance, out_bf16=True):
     return bf16_rne(out) if out_bf16 else out
 
 
+def controlnet_residual_add(h, residuals, out_bf16=True):
+    """Where ControlNet outputs enter the backbone (Section 2, "ControlNet": the outputs are
+    incorporated into the skip connections and the middle block, and those of several
+    ControlNets are first summed): out = h + (r_1 + r_2 + ... + r_n), the sum formed first,
+    left to right, every addition rounded to float32, then bfloat16 (nearest even) if asked.
+    With no residual the result is h."""
+    hf = np.asarray(h, dtype=np.float32)
+    if len(residuals) == 0:
+        out = hf.copy()
+    else:
+        s = np.asarray(residuals[0], dtype=np.float32)
+        for r in residuals[1:]:
+            s = (s + np.asarray(r, dtype=np.float32)).astype(np.float32)
+        out = (hf + s).astype(np.float32)
+    return bf16_rne(out) if out_bf16 else out
+
+
 def bal_timeline(load_done, step_time, n_steps, k, patch_time=0.0):
     """Bounded asynchronous LoRA loading as a timeline (Section 4.2): the adapters finish
     loading `load_done` seconds after the request arrives (the latest of them, since they

@@ -471,3 +471,29 @@ def test_generator_is_seeded_and_shaped():
     n = sum(c for c, _, _ in G.PATCH_SWEEP)
     elems = sum(c * o * i for c, o, i in G.PATCH_SWEEP)
     assert n == 310 and elems == 830_668_800
+
+
+def test_controlnet_residual_add_special_cases():
+    # Section 2, "ControlNet": several ControlNets' outputs are summed, then applied to the backbone tensor
+    rng = np.random.default_rng(11)
+    h = O.bf16_rne(rng.standard_normal((5, 33)).astype(np.float32))
+    rs = [O.bf16_rne(rng.standard_normal((5, 33)).astype(np.float32)) for _ in range(3)]
+    assert O.controlnet_residual_add(h, []).tobytes() == h.tobytes()                       # nothing to add
+    assert O.controlnet_residual_add(h, [np.zeros_like(h)] * 3).tobytes() == h.tobytes()
+    one = O.controlnet_residual_add(h, rs[:1], out_bf16=False)
+    assert one.tobytes() == (h + rs[0]).astype(np.float32).tobytes()                        # one ControlNet: a plain add
+    # against float64: three float32 additions of O(1) values
+    ref = h.astype(np.float64) + sum(r.astype(np.float64) for r in rs)
+    got = O.controlnet_residual_add(h, rs, out_bf16=False)
+    assert np.abs(got - ref).max() <= 4 * 2.0 ** -23 * np.abs(ref).max()
+    # small integers are exact whatever the order
+    hi = np.array([[1.0, -2.0, 8.0]], np.float32)
+    assert O.controlnet_residual_add(hi, [np.array([[2.0, 2.0, -3.0]], np.float32), np.array([[4.0, 1.0, -5.0]], np.float32)],
+                                     out_bf16=False).tolist() == [[7.0, 1.0, 0.0]]
+    # the ControlNets' outputs are summed first: 2^24 + (1 + 1) is exact, (2^24 + 1) + 1 is not
+    big = np.array([2.0 ** 24], np.float32)
+    u = np.array([1.0], np.float32)
+    assert O.controlnet_residual_add(big, [u, u], out_bf16=False)[0] == np.float32(2.0 ** 24 + 2)
+    # a dropped term or a flipped sign is seen
+    assert rel_err(O.controlnet_residual_add(h, rs[:2], out_bf16=False), got) > 0.1
+    assert rel_err(O.controlnet_residual_add(h, [rs[0], rs[1], -rs[2]], out_bf16=False), got) > 0.1
