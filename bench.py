@@ -323,6 +323,19 @@ def main() -> int:
     out["cfg_combine"] = {"elements": lat[0].numel(), "us": round(1e3 * float(np.median(time_events(lambda: B.cfg_combine(lat[0], lat[1], 7.5, out=lout), 20))), 2),
                           "note": "launch-bound: 384 KiB of traffic"}
 
+    # ------------------------- ControlNet outputs summed into a skip connection (HBM-bound)
+    # the largest SDXL injection point at 1024 x 1024: [2, 320, 128, 128] bf16, three ControlNets
+    hsk = torch.randn(2 * 320 * 128 * 128, device="cuda").to(torch.bfloat16)
+    rsk = [torch.randn_like(hsk) for _ in range(3)]
+    osk = torch.empty_like(hsk)
+    B.controlnet_residual_add(hsk, rsk, out=osk)
+    rms = float(np.median(time_events(lambda: B.controlnet_residual_add(hsk, rsk, out=osk), 20)))
+    rbytes = hsk.numel() * 2.0 * (len(rsk) + 2)
+    out["controlnet_residual_add"] = {"workload": "skip_2x320x128x128_bf16_3_controlnets", "us": round(1e3 * rms, 2),
+                                      "gbs": round(rbytes / (rms * 1e-3) / 1e9, 1), "frac_of_hbm": round(rbytes / (rms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                      "bytes_per_element": 2 * (len(rsk) + 2)}
+    del hsk, rsk, osk
+
     # ---------------------------------------------------------------- measured ceilings
     # what this device sustains: a register-resident bf16 MFMA loop and a streaming fp32
     # copy, to set beside the vendor peaks the fractions above are quoted against

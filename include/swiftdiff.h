@@ -286,6 +286,19 @@ int sd_lora_unpatch_multi(const void* plan_dev, int32_t n, int64_t total_tiles, 
  *   eps_uncond, eps_cond, out   device bf16 [n]; out may alias either input; n elements */
 int sd_cfg_combine(const uint16_t* eps_uncond, const uint16_t* eps_cond, float guidance, uint16_t* out, size_t n, void* stream);
 
+/* ---- controlnet_residual_add -------------------------------------------------------------
+ * Where ControlNet outputs enter the backbone (Section 2, "ControlNet": the outputs go into the
+ * skip connections and the middle block; those of several ControlNets are summed first):
+ *   out = h + (r_1 + r_2 + ... + r_n),
+ * the sum formed left to right with one fp32 rounding per addition, then one more for "+ h",
+ * then bf16 (nearest even).  No ControlNet is part of this library: the residuals are inputs.
+ *   h, out       device bf16 [n]; out may alias h or any residual
+ *   residuals    HOST array of n_res device pointers, each bf16 [n]; read during the call only
+ *   n_res        0 .. SD_CONTROLNET_MAX (0: out = h); outside that range SD_EINVAL
+ * Hipmemcpy-free except for n_res == 0 with out != h (one device-to-device copy). */
+#define SD_CONTROLNET_MAX 8
+int sd_controlnet_residual_add(const uint16_t* h, const uint16_t* const* residuals, int32_t n_res, uint16_t* out, size_t n, void* stream);
+
 /* ---- bal: bounded asynchronous LoRA loading, host side ------------------------------------
  * Section 4.2, "Bounded asynchronous LoRA loading (BAL)": when a request arrives its adapters
  * load in the background, in parallel, while the base model early-starts denoising unpatched;

@@ -109,6 +109,7 @@ def _load() -> C.CDLL:
         "sd_lora_patch_multi": (C.c_int, [vp, i32, i64, vp]),
         "sd_lora_unpatch_multi": (C.c_int, [vp, i32, i64, vp]),
         "sd_cfg_combine": (C.c_int, [vp, vp, f32, vp, sz, vp]),
+        "sd_controlnet_residual_add": (C.c_int, [vp, C.POINTER(C.c_void_p), i32, vp, sz, vp]),
         "sd_bal_create": (vp, [i32, BAL_LOAD_FN, vp]),
         "sd_bal_start": (C.c_int, [vp]),
         "sd_bal_loaded": (C.c_int, [vp]),
@@ -132,7 +133,7 @@ EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_set_projec
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
            "sd_multi_lora_linear_workspace_bytes", "sd_multi_lora_linear_fwd", "sd_patch_plan_bytes",
            "sd_patch_plan_build", "sd_lora_patch", "sd_lora_unpatch", "sd_patch_multi_plan_bytes",
-           "sd_patch_multi_plan_build", "sd_lora_patch_multi", "sd_lora_unpatch_multi", "sd_cfg_combine", "sd_bal_create", "sd_bal_start",
+           "sd_patch_multi_plan_build", "sd_lora_patch_multi", "sd_lora_unpatch_multi", "sd_cfg_combine", "sd_controlnet_residual_add", "sd_bal_create", "sd_bal_start",
            "sd_bal_loaded", "sd_bal_before_step", "sd_bal_stats", "sd_bal_finish", "sd_bal_destroy"]
 
 
@@ -391,6 +392,13 @@ def lora_unpatch_multi(plan: PatchMultiPlan) -> None:
 def cfg_combine(eps_uncond: torch.Tensor, eps_cond: torch.Tensor, guidance: float, out=None) -> torch.Tensor:
     y = out if out is not None else torch.empty_like(eps_uncond)
     _check(_lib.sd_cfg_combine(_ptr(eps_uncond), _ptr(eps_cond), float(guidance), _ptr(y), eps_uncond.numel(), _stream()))
+    return y
+
+
+def controlnet_residual_add(h: torch.Tensor, residuals: Sequence[torch.Tensor], out=None) -> torch.Tensor:
+    y = out if out is not None else torch.empty_like(h)
+    ptrs = (C.c_void_p * max(len(residuals), 1))(*[_ptr(r) for r in residuals])
+    _check(_lib.sd_controlnet_residual_add(_ptr(h), ptrs, len(residuals), _ptr(y), h.numel(), _stream()))
     return y
 
 

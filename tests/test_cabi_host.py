@@ -94,6 +94,13 @@ def test_patch_plan_build_validates_on_host(B):
     # cfg_combine: null pointers with n > 0
     assert L.sd_cfg_combine(None, None, 7.5, None, 16, None) == -1
     assert L.sd_cfg_combine(None, None, 7.5, None, 0, None) == 0
+    # controlnet_residual_add: count out of range, null pointers with n > 0, nothing to do with n == 0
+    assert L.sd_controlnet_residual_add(None, None, 9, None, 16, None) == -1
+    assert L.sd_controlnet_residual_add(None, None, -1, None, 0, None) == -1
+    assert L.sd_controlnet_residual_add(None, None, 2, None, 16, None) == -1
+    assert L.sd_controlnet_residual_add(None, None, 2, None, 0, None) == 0
+    two = (C.c_void_p * 2)(0x1000, None)
+    assert L.sd_controlnet_residual_add(0x1000, two, 2, 0x2000, 16, None) == -1 and b"residual 1" in L.sd_last_error()
 
 
 def test_forward_calls_reject_bad_arguments_before_touching_the_device(B):

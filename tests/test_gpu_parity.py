@@ -470,6 +470,26 @@ def test_cfg_combine_bit_exact(B):
     assert host(out).tobytes() == O.cfg_combine(x[:n], x[n:], 3.0).tobytes()
 
 
+def test_controlnet_residual_add_bit_exact(B):
+    """Section 2, "ControlNet": the summed ControlNet outputs added to a skip-connection tensor."""
+    import torch
+    r = rng(37)
+    for n, nres in ((1, 1), (7, 3), (4096, 2), (2 * 320 * 64 * 64 + 5, 3), (65536, 8), (2049, 0)):
+        h = G.bf16_round(r.standard_normal(n).astype(np.float32))
+        rs = [G.bf16_round(r.standard_normal(n).astype(np.float32)) for _ in range(nres)]
+        got = B.controlnet_residual_add(dev(h, B), [dev(x, B) for x in rs])
+        assert host(got).tobytes() == O.controlnet_residual_add(h, rs).tobytes(), (n, nres)
+    # in place on the backbone tensor, residuals at unaligned offsets of one buffer
+    n = 1001
+    x = G.bf16_round(r.standard_normal(3 * n).astype(np.float32))
+    xd = dev(x, B)
+    out = B.controlnet_residual_add(xd[:n], [xd[n:2 * n], xd[2 * n:]], out=xd[:n])
+    assert host(out).tobytes() == O.controlnet_residual_add(x[:n], [x[n:2 * n], x[2 * n:]]).tobytes()
+    # more ControlNets than the entry point takes
+    with pytest.raises(B.SwiftDiffError):
+        B.controlnet_residual_add(xd[:n], [xd[n:2 * n]] * 9)
+
+
 def test_bal_orders_the_patch_inside_a_denoising_loop(B):
     """The serving loop of Section 4.2 in miniature: a projection reads the bf16 serving copy of an
     fp32 master weight; two adapters load in the background (gated so that they arrive during
