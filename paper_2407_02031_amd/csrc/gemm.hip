@@ -368,14 +368,38 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
                 }
             }
     }
+    // per-column bias of this lane's output columns: fetched now as well (raw bits, widened after
+    // the last MFMAs; a column past N reads the last valid one and is never stored)
+    const uint16_t* bias = P.bias;
+    uint32_t bv_raw[NOUT], bg_raw[NOUT];
+#pragma unroll
+    for (int nj = 0; nj < NOUT; ++nj) bv_raw[nj] = bg_raw[nj] = 0u;
+    if (bias && !P.bias_on_rows) {
+#pragma unroll
+        for (int nj = 0; nj < NOUT; ++nj) {
+            const int q = min(n0 + wn_out + nj * 32 + l32, N - 1);
+            bv_raw[nj] = bias[q];
+            if (GEGLU) bg_raw[nj] = bias[q + P.geglu_F];
+        }
+    }
     compute(st);
     __syncthreads();   // ring reads done before the epilogue reuses LDS
 
     // ---- epilogue
     float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
     const float alpha = P.alpha;
-    const uint16_t* bias = P.bias;
     int32_t* const sig = P.signal;
+    // a tile that lies inside the output with 16-byte-aligned rows takes straight-line code: all
+    // staged pieces read, then all residual pieces, then all stores (no per-lane bounds)
+    const bool full = ld_ok && m0 + BM <= Mp && n0 + BN_OUT <= N;
+    float bv[NOUT], bg[NOUT];
+#pragma unroll
+    for (int nj = 0; nj < NOUT; ++nj) {
+        // (opaque to the optimiser, which would otherwise widen right after the loads and wait for them there)
+        asm volatile("" : "+v"(bv_raw[nj]), "+v"(bg_raw[nj]));
+        bv[nj] = __uint_as_float(bv_raw[nj] << 16);
+        bg[nj] = __uint_as_float(bg_raw[nj] << 16);
+    }
 
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
@@ -385,22 +409,16 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
 #pragma unroll
             for (int cj = 0; cj < CB; ++cj) {
                 const int nj = cc * CB + cj;
-                const int q = n0 + wn_out + nj * 32 + l32;
-                float bv = 0.f, bg = 0.f;
-                if (bias && !P.bias_on_rows && q < N) {
-                    bv = bf16_to_f32(bias[q]);
-                    if (GEGLU) bg = bf16_to_f32(bias[q + P.geglu_F]);
-                }
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int rr = 8 * (v >> 2) + 4 * hi + (v & 3);
                     float val;
                     if (GEGLU) {
-                        const float a = alpha * acc[mi][2 * nj][v] + bv;
-                        const float gt = alpha * acc[mi][2 * nj + 1][v] + bg;
+                        const float a = alpha * acc[mi][2 * nj][v] + bv[nj];
+                        const float gt = alpha * acc[mi][2 * nj + 1][v] + bg[nj];
                         val = a * gelu_erf(gt);
                     } else {
-                        val = alpha * acc[mi][nj][v] + bv;
+                        val = alpha * acc[mi][nj][v] + bv[nj];
                     }
                     stage[rr * EPI_STRIDE + cj * 32 + l32] = val;
                 }
@@ -409,62 +427,119 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
             __builtin_amdgcn_wave_barrier();
             // 2) staging -> global: lane handles 4 consecutive columns of one row per pass
             const int q4 = n0 + wn_out + cc * CCOLS + lcol;
-            const bool vec_ok = ld_ok && (q4 + 4 <= N);   // 16-byte path: whole piece inside N, aligned rows
+            if (full) {
+                f32x4 val[NPASS];
 #pragma unroll
-            for (int pass = 0; pass < NPASS; ++pass) {
-                const int rr = pass * RPP + lr;
-                const int p = m0 + wm + mi * 32 + rr;
-                if (p < Mp && q4 < N) {
-                    f32x4 val = *reinterpret_cast<const f32x4*>(stage + rr * EPI_STRIDE + lcol);
-                    if (bias && P.bias_on_rows) val += bf16_to_f32(bias[p]);
-                    const int64_t oi = (int64_t)p * P.ldy + q4;
-                    const int64_t ri = (int64_t)p * P.ldr + q4;
-                    if (y_f32) {
-                        float* yp = static_cast<float*>(P.y) + oi;
-                        const float* rp = static_cast<const float*>(P.res);
-                        if (vec_ok) {
-                            if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
-                            else if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
-                            *reinterpret_cast<f32x4*>(yp) = val;
-                        } else {
+                for (int pass = 0; pass < NPASS; ++pass)
+                    val[pass] = *reinterpret_cast<const f32x4*>(stage + (pass * RPP + lr) * EPI_STRIDE + lcol);
+                const int p0 = m0 + wm + mi * 32 + lr;          // row of pass 0; pass k is RPP * k rows further
+                if (bias && P.bias_on_rows) {
+                    float br[NPASS];
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (q4 + e < N) yp[e] = val[e] + (rp ? rp[ri + e] : 0.f);
-                        }
+                    for (int pass = 0; pass < NPASS; ++pass) br[pass] = bf16_to_f32(bias[p0 + pass * RPP]);
+#pragma unroll
+                    for (int pass = 0; pass < NPASS; ++pass) val[pass] += br[pass];
+                }
+                if (P.res) {
+                    if (RES32 && res_pre) {
+#pragma unroll
+                        for (int pass = 0; pass < NPASS; ++pass) val[pass] += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
+                    } else if (P.res_f32) {
+                        const float* rf = static_cast<const float*>(P.res) + (int64_t)p0 * P.ldr + q4;
+                        f32x4 r[NPASS];
+#pragma unroll
+                        for (int pass = 0; pass < NPASS; ++pass) r[pass] = *reinterpret_cast<const f32x4*>(rf + (int64_t)(pass * RPP) * P.ldr);
+#pragma unroll
+                        for (int pass = 0; pass < NPASS; ++pass) val[pass] += r[pass];
                     } else {
-                        uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
-                        const uint16_t* rp = static_cast<const uint16_t*>(P.res);
-                        if (P.res_f32 && rp) {      // fp32 residual stream into a bf16 output
-                            const float* rf = static_cast<const float*>(P.res);
-                            if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
-                            else if (vec_ok) val += *reinterpret_cast<const f32x4*>(rf + ri);
-                            else
+                        const uint16_t* rb = static_cast<const uint16_t*>(P.res) + (int64_t)p0 * P.ldr + q4;
+                        u32x2 r[NPASS];
+#pragma unroll
+                        for (int pass = 0; pass < NPASS; ++pass) r[pass] = *reinterpret_cast<const u32x2*>(rb + (int64_t)(pass * RPP) * P.ldr);
+#pragma unroll
+                        for (int pass = 0; pass < NPASS; ++pass) {
+                            val[pass][0] += bf16lo_to_f32(r[pass][0]); val[pass][1] += bf16hi_to_f32(r[pass][0]);
+                            val[pass][2] += bf16lo_to_f32(r[pass][1]); val[pass][3] += bf16hi_to_f32(r[pass][1]);
+                        }
+                    }
+                }
+                if (y_f32) {
+                    float* yp = static_cast<float*>(P.y) + (int64_t)p0 * P.ldy + q4;
+#pragma unroll
+                    for (int pass = 0; pass < NPASS; ++pass) *reinterpret_cast<f32x4*>(yp + (int64_t)(pass * RPP) * P.ldy) = val[pass];
+                } else {
+                    uint16_t* yp = static_cast<uint16_t*>(P.y) + (int64_t)p0 * P.ldy + q4;
+#pragma unroll
+                    for (int pass = 0; pass < NPASS; ++pass) {
+                        bf16x4 o;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[pass][e];
+                        uint16_t* const yq = yp + (int64_t)(pass * RPP) * P.ldy;
+                        if (sig)   // device-scope store: read by tiles of this launch on other XCDs
+                            __hip_atomic_store(reinterpret_cast<uint64_t*>(yq), __builtin_bit_cast(uint64_t, o), __ATOMIC_RELAXED,
+                                               __HIP_MEMORY_SCOPE_AGENT);
+                        else
+                            *reinterpret_cast<bf16x4*>(yq) = o;
+                    }
+                }
+            } else {
+                const bool vec_ok = ld_ok && (q4 + 4 <= N);   // 16-byte path: whole piece inside N, aligned rows
+#pragma unroll
+                for (int pass = 0; pass < NPASS; ++pass) {
+                    const int rr = pass * RPP + lr;
+                    const int p = m0 + wm + mi * 32 + rr;
+                    if (p < Mp && q4 < N) {
+                        f32x4 val = *reinterpret_cast<const f32x4*>(stage + rr * EPI_STRIDE + lcol);
+                        if (bias && P.bias_on_rows) val += bf16_to_f32(bias[p]);
+                        const int64_t oi = (int64_t)p * P.ldy + q4;
+                        const int64_t ri = (int64_t)p * P.ldr + q4;
+                        if (y_f32) {
+                            float* yp = static_cast<float*>(P.y) + oi;
+                            const float* rp = static_cast<const float*>(P.res);
+                            if (vec_ok) {
+                                if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
+                                else if (rp) val += *reinterpret_cast<const f32x4*>(rp + ri);
+                                *reinterpret_cast<f32x4*>(yp) = val;
+                            } else {
 #pragma unroll
                                 for (int e = 0; e < 4; ++e)
-                                    if (q4 + e < N) val[e] += rf[ri + e];
-                            rp = nullptr;
-                        }
-                        if (vec_ok) {
-                            if (rp) {
-                                const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
-                                val[0] += bf16lo_to_f32(rv[0]); val[1] += bf16hi_to_f32(rv[0]);
-                                val[2] += bf16lo_to_f32(rv[1]); val[3] += bf16hi_to_f32(rv[1]);
+                                    if (q4 + e < N) yp[e] = val[e] + (rp ? rp[ri + e] : 0.f);
                             }
-                            bf16x4 o;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
-                            if (sig)   // device-scope store: read by tiles of this launch on other XCDs
-                                __hip_atomic_store(reinterpret_cast<uint64_t*>(yp), __builtin_bit_cast(uint64_t, o), __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                            else
-                                *reinterpret_cast<bf16x4*>(yp) = o;
                         } else {
+                            uint16_t* yp = static_cast<uint16_t*>(P.y) + oi;
+                            const uint16_t* rp = static_cast<const uint16_t*>(P.res);
+                            if (P.res_f32 && rp) {      // fp32 residual stream into a bf16 output
+                                const float* rf = static_cast<const float*>(P.res);
+                                if (RES32 && res_pre) val += rpre[RES32 ? mi : 0][RES32 ? cc : 0][RES32 ? pass : 0];
+                                else if (vec_ok) val += *reinterpret_cast<const f32x4*>(rf + ri);
+                                else
 #pragma unroll
-                            for (int e = 0; e < 4; ++e)
-                                if (q4 + e < N) {
-                                    const float f = val[e] + (rp ? bf16_to_f32(rp[ri + e]) : 0.f);
-                                    yp[e] = __builtin_bit_cast(uint16_t, (__bf16)f);
+                                    for (int e = 0; e < 4; ++e)
+                                        if (q4 + e < N) val[e] += rf[ri + e];
+                                rp = nullptr;
+                            }
+                            if (vec_ok) {
+                                if (rp) {
+                                    const u32x2 rv = *reinterpret_cast<const u32x2*>(rp + ri);
+                                    val[0] += bf16lo_to_f32(rv[0]); val[1] += bf16hi_to_f32(rv[0]);
+                                    val[2] += bf16lo_to_f32(rv[1]); val[3] += bf16hi_to_f32(rv[1]);
                                 }
+                                bf16x4 o;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) o[e] = (__bf16)val[e];
+                                if (sig)   // device-scope store: read by tiles of this launch on other XCDs
+                                    __hip_atomic_store(reinterpret_cast<uint64_t*>(yp), __builtin_bit_cast(uint64_t, o), __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+                                else
+                                    *reinterpret_cast<bf16x4*>(yp) = o;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e)
+                                    if (q4 + e < N) {
+                                        const float f = val[e] + (rp ? bf16_to_f32(rp[ri + e]) : 0.f);
+                                        yp[e] = __builtin_bit_cast(uint16_t, (__bf16)f);
+                                    }
+                            }
                         }
                     }
                 }
