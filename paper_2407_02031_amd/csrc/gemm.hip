@@ -557,6 +557,17 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
     }
 }
 
+// The group's header (everything before p[]) and one problem record are fetched as a few wide
+// scalar loads (dword-aligned vector types)
+typedef uint32_t u32x16u __attribute__((ext_vector_type(16), aligned(4)));
+typedef uint32_t u32x8u __attribute__((ext_vector_type(8), aligned(4)));
+typedef uint32_t u32x4u __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2u __attribute__((ext_vector_type(2), aligned(4)));
+struct alignas(8) ProblemWords { uint32_t w[44]; };
+static_assert(offsetof(GemmGroup, p) == 88 && offsetof(GemmGroup, first_tile) == 24 && offsetof(GemmGroup, zero_ptr) == 16 &&
+              offsetof(GemmGroup, n_lead) == 8 && offsetof(GemmGroup, zero_n) == 12, "header layout");
+static_assert(sizeof(GemmProblem) == sizeof(ProblemWords), "problem record size");
+
 template <int BM, int BN, int BK, int WGM, int WGN, int STAGES, bool GEGLU, bool GUARD, bool RES32>
 __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WGN, STAGES>())) void gemm_kernel(const GemmGroup g) {
     constexpr int NW = WGM * WGN;
@@ -569,26 +580,48 @@ __global__ __launch_bounds__(64 * WGM * WGN, (gemm_min_waves<BM, BN, BK, WGM, WG
     // The tiles of signalling problems (down-projections that tiles of this same launch wait
     // for) come first and are dealt round-robin: they are the first workgroups dispatched on
     // every XCD, so all of them are running, or done, before any tile can wait for them.
+    // Kernel arguments arrive through scalar loads of ~0.25 us each, and the compiler issues a
+    // load next to its first use: left alone, a workgroup pays six or seven such rounds one after
+    // the other before its first operand load.  Two rounds are forced instead: the header in one
+    // batch (made opaque right away, so no load can sink below), then the whole problem record.
+    const uint32_t* const hw = reinterpret_cast<const uint32_t*>(&g);
+    u32x16u ha = *reinterpret_cast<const u32x16u*>(hw);
+    u32x4u hb = *reinterpret_cast<const u32x4u*>(hw + 16);
+    u32x2u hc = *reinterpret_cast<const u32x2u*>(hw + 20);
+    uint32_t grid = gridDim.x;     // one more kernel argument (the launch geometry): same batch
+    asm volatile("" : "+s"(ha), "+s"(hb), "+s"(hc), "+s"(grid));
+    const int lead = (int)ha[2], zero_n = (int)ha[3], np = (int)ha[0];
+    int32_t* const zero_ptr = reinterpret_cast<int32_t*>(((uint64_t)ha[5] << 32) | ha[4]);
     int tile = blockIdx.x;
     {
-        const int lead = g.n_lead;
-        const int rest = (int)gridDim.x - lead;
+        const int rest = (int)grid - lead;
         if (tile >= lead && (rest & 7) == 0) {
             const int r = tile - lead;
             tile = lead + (r & 7) * (rest >> 3) + (r >> 3);
         }
     }
-    // flags of the next dependent launch, a few words per workgroup: nothing reads them before this kernel ends
-    for (int i = blockIdx.x * (64 * NW) + threadIdx.x; i < g.zero_n; i += gridDim.x * (64 * NW)) g.zero_ptr[i] = 0;
-    // Kernel arguments come through dependent scalar loads of ~0.25 us each: the table of
-    // first tiles is one load, problem 0 is fetched alongside it, and only tiles of a later
-    // problem pay a second round.
     int pi = 0;
 #pragma unroll
-    for (int i = 1; i < GEMM_MAX_PROBLEMS; ++i)
-        if (i < g.n && tile >= g.first_tile[i]) pi = i;
-    GemmProblem P = g.p[0];
-    if (pi != 0) P = g.p[pi];
+    for (int i = 1; i < GEMM_MAX_PROBLEMS; ++i) {
+        const int ft = (int)(i < 10 ? ha[6 + i] : i < 14 ? hb[i - 10] : hc[i - 14]);
+        if (i < np && tile >= ft) pi = i;
+    }
+    const uint32_t* const pw = reinterpret_cast<const uint32_t*>(&g.p[pi]);
+    u32x16u ra = *reinterpret_cast<const u32x16u*>(pw);
+    u32x16u rb = *reinterpret_cast<const u32x16u*>(pw + 16);
+    u32x8u rc = *reinterpret_cast<const u32x8u*>(pw + 32);
+    u32x4u rd = *reinterpret_cast<const u32x4u*>(pw + 40);
+    asm volatile("" : "+s"(ra), "+s"(rb), "+s"(rc), "+s"(rd));
+    ProblemWords words;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { words.w[i] = ra[i]; words.w[16 + i] = rb[i]; }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) words.w[32 + i] = rc[i];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) words.w[40 + i] = rd[i];
+    const GemmProblem P = __builtin_bit_cast(GemmProblem, words);
+    // flags of the next dependent launch, a few words per workgroup: nothing reads them before this kernel ends
+    for (int i = blockIdx.x * (64 * NW) + threadIdx.x; i < zero_n; i += (int)grid * (64 * NW)) zero_ptr[i] = 0;
     if constexpr (BN > DOWN_BN) {
         if (P.signal) {
             gemm_tile<BM, DOWN_BN, BK, WGM, WGN, down_stages<BM, BN, BK, STAGES>(), false, GUARD, false>(P, tile, lds);
