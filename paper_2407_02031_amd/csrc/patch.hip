@@ -28,10 +28,10 @@ __device__ __forceinline__ void nt_store4(float* p, float4 v) {
 
 // These kernels stream: what limits them is how well HBM copes with the mix of requests in
 // flight, and past a point more wavefronts per CU make that worse (more streams interleaved per
-// channel).  The launches therefore ask for dynamic LDS that no kernel touches, only to cap the
-// workgroups per CU (160 KB of LDS per CU): three for the patch pass, six for the copies back.
-// Measured on the 310-matrix sweep: +2.5 % and +5 %; one step further either way loses 10 %.
-constexpr int PATCH_THROTTLE_LDS = 48 * 1024;
+// channel).  The copies back therefore ask for dynamic LDS that no kernel touches, only to cap
+// the workgroups per CU (160 KB of LDS per CU) at six: +5 % on the 310-matrix sweep.  The patch
+// pass is capped by its registers at four workgroups per CU, which is where it runs best (a cap
+// of three cost 4 % once the undo record went out first; two cost 15 %).
 constexpr int UNPATCH_THROTTLE_LDS = 24 * 1024;
 
 struct PatchPlanEntry {
@@ -66,6 +66,10 @@ __device__ __forceinline__ int find_entry(const PatchPlanEntry* __restrict__ pla
     return lo;
 }
 
+// k pairs per batch of fragment loads in the rank-32 path.  Measured on the 310-matrix sweep:
+// 8 beats 16 (all fragments up front) by 1 % with one adapter and by 10 % with two, and beats 4
+// and 2; requesting a batch while the batch before it multiplies (double registers) lost.
+constexpr int FRAG_KP = 8;
 // acc[j][v] += sum_k B[row(v)][k] * A[k][col + j] for one adapter on a full tile (all 32 rows
 // and 128 columns inside the matrix, in % 4 == 0): lane l32 supplies B row r0 + l32 and the
 // four A columns col..col+3, k pair (2 kp + hi) per MFMA.
@@ -75,20 +79,23 @@ __device__ __forceinline__ void delta_full(const float* __restrict__ A, const fl
     const float* ap = A + (size_t)hi * in + col;
     const int kp_n = r >> 1;
     if (r == 32) {
-        // the common rank: every A and B fragment is requested up front (they come out
-        // of L2), so the 64 MFMAs run back to back while the W tile arrives from HBM
-        float bv[16];
-        float4 av[16];
+        // the common rank: the A and B fragments (they come out of L2) are requested in two
+        // batches of FRAG_KP k pairs, 32 MFMAs behind each
+#pragma unroll 1
+        for (int k0 = 0; k0 < 16; k0 += FRAG_KP) {
+            float bv[FRAG_KP];
+            float4 av[FRAG_KP];
 #pragma unroll
-        for (int kp = 0; kp < 16; ++kp) bv[kp] = bp[2 * kp];
+            for (int kp = 0; kp < FRAG_KP; ++kp) bv[kp] = bp[2 * (k0 + kp)];
 #pragma unroll
-        for (int kp = 0; kp < 16; ++kp) av[kp] = *reinterpret_cast<const float4*>(ap + (size_t)(2 * kp) * in);
+            for (int kp = 0; kp < FRAG_KP; ++kp) av[kp] = *reinterpret_cast<const float4*>(ap + (size_t)(2 * (k0 + kp)) * in);
 #pragma unroll
-        for (int kp = 0; kp < 16; ++kp) {
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].x, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].y, acc[1], 0, 0, 0);
-            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].z, acc[2], 0, 0, 0);
-            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].w, acc[3], 0, 0, 0);
+            for (int kp = 0; kp < FRAG_KP; ++kp) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].y, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].z, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], av[kp].w, acc[3], 0, 0, 0);
+            }
         }
     } else {
 #pragma unroll 4
@@ -404,7 +411,7 @@ static int patch_launch(bool undo, const void* plan_dev, int32_t n, int64_t tota
     const PatchPlanEntry* plan = static_cast<const PatchPlanEntry*>(plan_dev);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (undo) hipLaunchKernelGGL(lora_unpatch_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), UNPATCH_THROTTLE_LDS, s, plan, n);
-    else hipLaunchKernelGGL(lora_patch_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), PATCH_THROTTLE_LDS, s, plan, n);
+    else hipLaunchKernelGGL(lora_patch_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), 0, s, plan, n);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }
