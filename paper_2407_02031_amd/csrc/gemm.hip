@@ -29,20 +29,23 @@ __device__ __forceinline__ int swz(int row, int chunk) {
     return CPR == 8 ? (chunk ^ ((row >> 1) & 7)) : (chunk ^ ((row >> 2) & 3));
 }
 
-// erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7), far below bf16 resolution
-__device__ __forceinline__ float erf_as(float x) {
-    const float ax = fabsf(x);
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+// GELU, exact (erf) form, with erf by Abramowitz & Stegun 7.1.26 (|error| <= 1.5e-7, far below
+// bf16 resolution): erf(|x|) = 1 - (a1 t + ... + a5 t^5) exp(-x^2), t = 1 / (1 + p |x|).
+// With x = z / sqrt(2) and h = z / 2:  gelu(z) = h (1 + erf(x)) = h + |h| erf(|x|), because erf is
+// odd and h has the sign of x: no sign transfer, and sqrt(1/2) folds into the constants.
+__device__ __forceinline__ float gelu_erf(float z) {
+    const float az = fabsf(z);
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, az, 1.0f));
     float p = fmaf(1.061405429f, t, -1.453152027f);
     p = fmaf(p, t, 1.421413741f);
     p = fmaf(p, t, -0.284496736f);
     p = fmaf(p, t, 0.254829592f);
     p *= t;
-    const float e = __builtin_amdgcn_exp2f(-1.44269504088896340736f * ax * ax);
-    const float r = fmaf(-p, e, 1.0f);
-    return copysignf(r, x);
+    const float e = __builtin_amdgcn_exp2f((-0.5f * 1.44269504088896340736f * z) * z);
+    const float r = fmaf(-p, e, 1.0f);          // erf(|x|) in [0, 1]
+    const float h = 0.5f * z;
+    return fmaf(fabsf(h), r, h);
 }
-__device__ __forceinline__ float gelu_erf(float z) { return 0.5f * z * (1.0f + erf_as(z * 0.70710678118654752440f)); }
 
 constexpr int EPI_STRIDE = 72;   // floats per staged row: 4 rows apart differ by 128 B mod 256 (no bank overlap)
 
