@@ -524,7 +524,6 @@ extern "C" int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype, const
     if ((rc = check_proj(q, "attn_block q", C)) || (rc = check_proj(k, "attn_block k", Kkv)) ||
         (rc = check_proj(v, "attn_block v", Kkv)) || (rc = check_proj(o, "attn_block o", C)))
         return rc;
-    SD_REQUIRE(!v->bias, SD_EUNSUPPORTED, "attn_block: the v projection takes no bias");
     if (Bn == 0 || T == 0) return SD_OK;
     SD_REQUIRE(x && y && aligned16(x) && aligned16(y) && aligned16(ctx), SD_EINVAL, "attn_block: x/y/ctx null or misaligned");
     const sd_proj* ps[4] = {q, k, v, o};
@@ -646,7 +645,6 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
             (rc = check_proj(&b.v2, "v2", Dc)) || (rc = check_proj(&b.o2, "o2", C)) || (rc = check_proj(&b.ff1, "ff1", C)) ||
             (rc = check_proj(&b.ff2, "ff2", 4 * C)))
             return rc;
-        SD_REQUIRE(!b.v1.bias && !b.v2.bias, SD_EUNSUPPORTED, "block %d: v projections take no bias", i);
         const sd_proj* ps[10] = {&b.q1, &b.k1, &b.v1, &b.o1, &b.q2, &b.k2, &b.v2, &b.o2, &b.ff1, &b.ff2};
         const int r = rmax_of(ps, 10);
         if (r > rmax) rmax = r;

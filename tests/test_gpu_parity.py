@@ -292,6 +292,36 @@ def test_attn_block_ragged_sizes(B, Bn, T, Tc, C, heads, rank):
     assert B.gemm_dep_timeouts() == 0
 
 
+@pytest.mark.parametrize("T,Tc", [(256, 128), (200, 77)])
+def test_attn_block_with_biased_q_k_v(B, T, Tc):
+    """A projection record may carry a bias whatever its role.  With one on k the keys cannot leave
+    their projection pre-multiplied by the softmax scale (the attention kernel scales the scores
+    itself), and one on v is a per-row bias of the transposed v^T problem; T = 256 gives tiles that
+    lie inside the output, T = 200 ragged ones."""
+    import torch
+    cfg = small_cfg(Bn=2, T=T, Tc=Tc, C=128, heads=2, r=16)
+    p = G.make_stack_inputs(cfg, seed=11)
+    blk = p["blocks"][0]
+    r = rng(T + 1)
+    h = r.standard_normal(p["x"].shape).astype(np.float32)
+    for cross in (False, True):
+        names = ("q2", "k2", "v2", "o2", "ln2_g", "ln2_b") if cross else ("q1", "k1", "v1", "o1", "ln1_g", "ln1_b")
+        pq, pk, pv, po, g, b = (blk[n] for n in names)
+        pq, pk, pv = (dict(q, b=G.bf16_round((0.5 * r.standard_normal(q["W"].shape[0])).astype(np.float32))) for q in (pq, pk, pv))
+        ctx = p["ctx"] if cross else None
+        ref = O.attn_sublayer(h, ctx, g, b, pq, pk, pv, po, cfg.heads)
+        y = B.attn_block_fwd(torch.from_numpy(h).cuda(), dev(ctx, B) if cross else None, dev(g, B), dev(b, B), B.Proj.from_numpy(pq),
+                             B.Proj.from_numpy(pk), B.Proj.from_numpy(pv), B.Proj.from_numpy(po), cfg.heads)
+        assert rel_err(host(y) - h, ref - h) <= BF16_TOL, (cross,)
+        # the q and v biases matter at this tolerance; a k bias shifts every score of a query by
+        # the same amount, which softmax removes (so the GPU's scaling of biased keys is what is tested)
+        for drop in range(3):
+            qs = [pq, pk, pv]
+            qs[drop] = dict(qs[drop], b=None)
+            e = rel_err(O.attn_sublayer(h, ctx, g, b, *qs, po, cfg.heads) - h, ref - h)
+            assert (e < 1e-9) if drop == 1 else (e > 3 * BF16_TOL), (cross, drop, e)
+
+
 def test_ff_block_matches_oracle(B):
     import torch
     cfg = small_cfg(T=150, C=192, heads=3)
@@ -335,6 +365,26 @@ def test_stack_small_ragged(B):
     ref = O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads)
     assert rel_err(got, ref) <= BF16_TOL
     assert rel_err(got - p["x"], ref - p["x"]) <= 2 * BF16_TOL     # what the stack adds, bf16 output rounding included
+
+
+def test_stack_with_biased_q_k_v(B):
+    """SDXL's q, k, v carry no bias, but a projection record may: the stack takes them too (the
+    text keys / values projected ahead inside the self-attention launches included)."""
+    cfg = small_cfg(T=200, depth=2)
+    p = G.make_stack_inputs(cfg, seed=4)
+    r = rng(40)
+    for blk in p["blocks"]:
+        for name in ("q1", "k1", "v1", "q2", "k2", "v2"):
+            blk[name] = dict(blk[name], b=G.bf16_round((0.5 * r.standard_normal(blk[name]["W"].shape[0])).astype(np.float32)))
+    got = host(B.spatial_transformer_fwd(dev(p["x"], B), dev(p["ctx"], B), B.StackParams(p), cfg.heads))
+    ref = O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads)
+    assert rel_err(got - p["x"], ref - p["x"]) <= 2 * BF16_TOL
+    # without the value biases the oracle's result is far away
+    for blk in p["blocks"]:
+        blk["v1"] = dict(blk["v1"], b=None)
+        blk["v2"] = dict(blk["v2"], b=None)
+    e = rel_err(O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads) - p["x"], ref - p["x"])
+    assert e > 6 * BF16_TOL, e
 
 
 def test_stack_tiny_config(B):
