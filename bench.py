@@ -376,12 +376,15 @@ def main() -> int:
     # --------------------------------------------------------------------- CPU baseline
     if not args.no_cpu_baseline:
         from oracle import sdxl_block_oracle as O
-        c0 = time.perf_counter()
-        O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads)
+        # whole stack calls of the same workload until about 10 s of CPU work are done (at least one)
+        calls, c0 = 0, time.perf_counter()
+        while calls == 0 or (time.perf_counter() - c0 < 10.0 and calls < 8):
+            O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads)
+            calls += 1
         c1 = time.perf_counter()
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        out["cpu_baseline"] = {"value": round(flops / (c1 - c0) / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-                               "sample": "1 full stack call of the same workload (fp64 numpy oracle), %.1f s" % (c1 - c0)}
+        out["cpu_baseline"] = {"value": round(calls * flops / (c1 - c0) / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+                               "sample": "%d full stack call(s) of the same workload (fp64 numpy oracle), %.1f s" % (calls, c1 - c0)}
     out["context"] = "paper reports up to 7.8x latency / 1.6x throughput for SDXL end to end on H800; no kernel-level figure"
     print(json.dumps(out))
     return 0
