@@ -362,8 +362,15 @@ def main() -> int:
     B.ceiling_copy_f32(csrc, cdst)
     cb = float(np.median(time_events(lambda: B.ceiling_copy_f32(csrc, cdst), 5)))
     copy_large = 8.0 * big / (cb * 1e-3) / 1e9
+    # ... and with two destinations: one read and two writes per element, the patch pass's mix
+    cdst2 = torch.empty_like(csrc)
+    B.ceiling_copy_1r2w_f32(csrc, cdst, cdst2)
+    c2 = float(np.median(time_events(lambda: B.ceiling_copy_1r2w_f32(csrc, cdst, cdst2), 5)))
+    copy_1r2w = 12.0 * big / (c2 * 1e-3) / 1e9
+    del cdst2
     out["ceilings"] = {"mfma_bf16_tflops": round(mfma_ceiling, 1), "copy_f32_gbs": round(copy_ceiling, 1),
                        "copy_f32_gbs_at_patch_footprint": round(copy_large, 1),
+                       "copy_1r2w_f32_gbs_at_patch_footprint": round(copy_1r2w, 1),
                        "value_frac_of_mfma_ceiling": round(tflops / mfma_ceiling, 4),
                        "dominant_kernel_frac_of_mfma_ceiling": round(kernels[dom]["tflops"] / mfma_ceiling, 4)}
     if "patch" in out:
@@ -371,6 +378,7 @@ def main() -> int:
         out["ceilings"]["unpatch_frac_of_copy_ceiling"] = round(out["patch"]["unpatch_gbs"] / copy_ceiling, 4)
         out["ceilings"]["patch_frac_of_copy_at_patch_footprint"] = round(out["patch"]["patch_gbs"] / copy_large, 4)
         out["ceilings"]["unpatch_frac_of_copy_at_patch_footprint"] = round(out["patch"]["unpatch_gbs"] / copy_large, 4)
+        out["ceilings"]["patch_frac_of_1r2w_copy_at_patch_footprint"] = round(out["patch"]["patch_gbs"] / copy_1r2w, 4)
     del csrc, cdst, cout
 
     # --------------------------------------------------------------------- CPU baseline

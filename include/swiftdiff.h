@@ -141,6 +141,9 @@ int sd_timing_disable(void);
  *   pointers, no overlap): 8 bytes of traffic per element. */
 int sd_ceiling_mfma_bf16(float* out, int32_t workgroups, int32_t iters, double* flops, void* stream);
 int sd_ceiling_copy_f32(const float* src, float* dst, size_t n, void* stream);
+/* the same with two destinations (dst0 = dst1 = src afterwards): one read and two writes per element, the
+ * traffic mix of the patch pass (W read, undo record and W' written) */
+int sd_ceiling_copy_1r2w_f32(const float* src, float* dst0, float* dst1, size_t n, void* stream);
 
 /* ---- lora_linear_fwd ------------------------------------------------------------------
  * y = epi( LN?(x) W^T + bias + scale * (LN?(x) A^T) B^T ) + residual

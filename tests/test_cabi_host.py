@@ -91,6 +91,11 @@ def test_patch_plan_build_validates_on_host(B):
     md[0].B[1] = 0x6000
     md[0].serving = 0x8004      # not 8-byte aligned
     assert L.sd_patch_multi_plan_build(md, 1, mhost.ctypes.data_as(C.c_void_p), mhost.nbytes, C.byref(tiles)) == -1
+    # the two-destination copy ceiling: null / misaligned pointers, n not a multiple of 4
+    assert L.sd_ceiling_copy_1r2w_f32(None, None, None, 16, None) == -1
+    assert L.sd_ceiling_copy_1r2w_f32(0x1000, 0x2000, 0x3004, 16, None) == -1
+    assert L.sd_ceiling_copy_1r2w_f32(0x1000, 0x2000, 0x3000, 6, None) == -1
+    assert L.sd_ceiling_copy_1r2w_f32(0x1000, 0x2000, 0x3000, 0, None) == 0
     # cfg_combine: null pointers with n > 0
     assert L.sd_cfg_combine(None, None, 7.5, None, 16, None) == -1
     assert L.sd_cfg_combine(None, None, 7.5, None, 0, None) == 0

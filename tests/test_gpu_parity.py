@@ -540,6 +540,18 @@ def test_controlnet_residual_add_bit_exact(B):
         B.controlnet_residual_add(xd[:n], [xd[n:2 * n]] * 9)
 
 
+def test_ceiling_copies_copy(B):
+    """The streaming-ceiling kernels of the benchmark are plain copies: every byte arrives, sizes
+    that are not a multiple of the grid's stride included."""
+    import torch
+    for n in (4, 1028, 128 * 4 * 131072 + 4 * 77):
+        src = torch.arange(n, device="cuda", dtype=torch.float32)
+        d0, d1, d2 = (torch.full((n,), -1.0, device="cuda") for _ in range(3))
+        B.ceiling_copy_f32(src, d0)
+        B.ceiling_copy_1r2w_f32(src, d1, d2)
+        assert torch.equal(d0, src) and torch.equal(d1, src) and torch.equal(d2, src), n
+
+
 def test_bal_orders_the_patch_inside_a_denoising_loop(B):
     """The serving loop of Section 4.2 in miniature: a projection reads the bf16 serving copy of an
     fp32 master weight; two adapters load in the background (gated so that they arrive during
