@@ -27,7 +27,7 @@ The block's internal structure (pre-LayerNorm self-attention, cross-attention to
 text context, GEGLU feed-forward, each with a residual connection, wrapped by
 GroupNorm + proj_in and proj_out + input) is the standard SDXL spatial transformer;
 the paper prints no shapes or formulas for it, so those parts are pinned by the
-mathematical properties listed in tests/test_oracle_pins.py, not by paper values.
+brute-force references and properties of tests/test_oracle_pins.py, not by paper values.
 
   * Section 3.1 (add-on usage table) and Section 4.2: a request carries one or two
     LoRAs, loaded in parallel and each merged into the base weights; several adapters
@@ -43,10 +43,14 @@ mathematical properties listed in tests/test_oracle_pins.py, not by paper values
 
 Parity pins: linear / lora_linear / layernorm / groupnorm / attention / gelu / geglu /
 lora_patch / multi_lora_linear are pinned by brute-force loops, closed forms and
-invariants.  `block` and `spatial_transformer` are compositions with no closed form:
-they are pinned through their parts plus structural identities (identity block,
-zero-adapter, batch independence, depth composition) — the paper prints no worked
-numbers for them.
+invariants.  `attn_sublayer`, `ff_sublayer`, `block` and `spatial_transformer` are
+pinned against the block's equations written out in plain Python loops (math module
+only) at toy size, a reference in which each plausible composition mistake (query or
+keys from the un-normalised stream, a missing LayerNorm, gamma and beta exchanged,
+sub-layers in another order, a dropped residual, the GEGLU halves exchanged) is shown to
+move the result, plus structural identities (identity block, zero adapter, batch
+independence, depth composition).  The paper prints no worked numbers for the block, so
+none of these is a paper value.
 """
 from __future__ import annotations
 

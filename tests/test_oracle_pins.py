@@ -497,3 +497,189 @@ def test_controlnet_residual_add_special_cases():
     # a dropped term or a flipped sign is seen
     assert rel_err(O.controlnet_residual_add(h, rs[:2], out_bf16=False), got) > 0.1
     assert rel_err(O.controlnet_residual_add(h, [rs[0], rs[1], -rs[2]], out_bf16=False), got) > 0.1
+
+
+# ------------------------------------- sub-layer composition, by brute force in plain Python
+# The block's equations (pre-LayerNorm self-attention, cross-attention to the text context,
+# GEGLU feed-forward, each added to the stream) written out with nested loops and the math
+# module only: no numpy contraction, no call into the oracle.  `mut` plants one mistake in
+# this reference, so that the test can show each of them would be seen:
+#   "q_from_h"      the query projected from the un-normalised stream
+#   "kv_from_h"     self-attention keys / values projected from h instead of LN(h)
+#   "ff_no_ln"      the feed-forward sub-layer without its LayerNorm
+#   "gamma_beta"    LayerNorm's gamma and beta exchanged
+#   "cross_first"   cross-attention before self-attention
+#   "no_residual"   a sub-layer's output replacing the stream instead of being added to it
+#   "gate_first"    GEGLU taking the first half as the gate
+def _py_matvec_rows(X, W, b=None):
+    return [[sum(x[k] * w[k] for k in range(len(x))) + (b[n] if b is not None else 0.0) for n, w in enumerate(W)] for x in X]
+
+
+def _py_proj(X, p):
+    Y = _py_matvec_rows(X, p["W"], p.get("b"))
+    if p.get("A") is not None:
+        Tm = _py_matvec_rows(X, p["A"])
+        U = _py_matvec_rows(Tm, p["B"])
+        Y = [[y + p["scale"] * u for y, u in zip(yr, ur)] for yr, ur in zip(Y, U)]
+    return Y
+
+
+def _py_layernorm(X, g, b, eps=1e-5):
+    out = []
+    for x in X:
+        mu = sum(x) / len(x)
+        var = sum((v - mu) ** 2 for v in x) / len(x)
+        out.append([(v - mu) / math.sqrt(var + eps) * g[i] + b[i] for i, v in enumerate(x)])
+    return out
+
+
+def _py_attention(Q, K, V, heads):
+    C = len(Q[0])
+    d = C // heads
+    out = [[0.0] * C for _ in Q]
+    for h in range(heads):
+        for i, q in enumerate(Q):
+            s = [sum(q[h * d + e] * k[h * d + e] for e in range(d)) / math.sqrt(d) for k in K]
+            mx = max(s)
+            w = [math.exp(v - mx) for v in s]
+            z = sum(w)
+            for e in range(d):
+                out[i][h * d + e] = sum(w[j] / z * V[j][h * d + e] for j in range(len(K)))
+    return out
+
+
+def _py_attn_sublayer(H, ctx, g, b, pq, pk, pv, po, heads, mut):
+    if mut == "gamma_beta":
+        g, b = b, g
+    Nrm = _py_layernorm(H, g, b)
+    src = Nrm if ctx is None else ctx
+    if mut == "kv_from_h" and ctx is None:
+        src = H
+    Q = _py_proj(H if mut == "q_from_h" else Nrm, pq)
+    Kk, Vv = _py_proj(src, pk), _py_proj(src, pv)
+    U = _py_proj(_py_attention(Q, Kk, Vv, heads), po)
+    if mut == "no_residual":
+        return U
+    return [[h + u for h, u in zip(hr, ur)] for hr, ur in zip(H, U)]
+
+
+def _py_ff_sublayer(H, g, b, p1, p2, mut):
+    if mut == "gamma_beta":
+        g, b = b, g
+    Nrm = H if mut == "ff_no_ln" else _py_layernorm(H, g, b)
+    U = _py_proj(Nrm, p1)
+    F = len(U[0]) // 2
+    if mut == "gate_first":
+        G_ = [[u[F + i] * (0.5 * u[i] * (1.0 + math.erf(u[i] / math.sqrt(2.0)))) for i in range(F)] for u in U]
+    else:
+        G_ = [[u[i] * (0.5 * u[F + i] * (1.0 + math.erf(u[F + i] / math.sqrt(2.0)))) for i in range(F)] for u in U]
+    Y = _py_proj(G_, p2)
+    return [[h + y for h, y in zip(hr, yr)] for hr, yr in zip(H, Y)]
+
+
+def _py_block(H, ctx, blk, heads, mut=None):
+    """H [Bn][T][C], ctx [Bn][Tc][Dc] as nested lists; every sample on its own."""
+    out = []
+    for hb, cb in zip(H, ctx):
+        def self_attn(h):
+            return _py_attn_sublayer(h, None, blk["ln1_g"], blk["ln1_b"], blk["q1"], blk["k1"], blk["v1"], blk["o1"], heads, mut)
+
+        def cross_attn(h):
+            return _py_attn_sublayer(h, cb, blk["ln2_g"], blk["ln2_b"], blk["q2"], blk["k2"], blk["v2"], blk["o2"], heads, mut)
+        h = cross_attn(hb) if mut == "cross_first" else self_attn(hb)
+        h = self_attn(h) if mut == "cross_first" else cross_attn(h)
+        out.append(_py_ff_sublayer(h, blk["ln3_g"], blk["ln3_b"], blk["ff1"], blk["ff2"], mut))
+    return out
+
+
+def _toy_block(seed=21):
+    """Bn=2, T=3, Tc=2, C=4, 2 heads of 2, Dc=3, F=16, rank 2, scale 0.5; every projection
+    biased (also q, k, v: a dropped bias would otherwise hide), gamma away from 1, beta
+    away from 0, unit-scale weights so that softmax is far from uniform."""
+    r = rng(seed)
+    C, Dc, F, rk = 4, 3, 16, 2
+
+    def pr(n_out, n_in):
+        return {"W": r.standard_normal((n_out, n_in)), "b": r.standard_normal(n_out), "A": r.standard_normal((rk, n_in)),
+                "B": r.standard_normal((n_out, rk)), "scale": 0.5}
+    blk = {}
+    for i in (1, 2, 3):
+        blk[f"ln{i}_g"] = 1.5 + 0.5 * r.standard_normal(C)
+        blk[f"ln{i}_b"] = 0.7 * r.standard_normal(C) + 0.3
+    blk.update(q1=pr(C, C), k1=pr(C, C), v1=pr(C, C), o1=pr(C, C), q2=pr(C, C), k2=pr(C, Dc), v2=pr(C, Dc), o2=pr(C, C),
+               ff1=pr(2 * F, C), ff2=pr(C, F))
+    h = r.standard_normal((2, 3, C)) * 1.3 + 0.4
+    ctx = r.standard_normal((2, 2, Dc))
+    return h, ctx, blk
+
+
+def _to_lists(blk):
+    return {k: ({kk: (vv.tolist() if isinstance(vv, np.ndarray) else vv) for kk, vv in v.items()} if isinstance(v, dict) else v.tolist())
+            for k, v in blk.items()}
+
+
+def test_sublayers_and_block_against_plain_python_loops():
+    h, ctx, blk = _toy_block()
+    L = _to_lists(blk)
+    heads = 2
+    # each sub-layer on its own, both samples
+    for b in range(2):
+        hb, cb = h[b].tolist(), ctx[b].tolist()
+        ref = _py_attn_sublayer(hb, None, L["ln1_g"], L["ln1_b"], L["q1"], L["k1"], L["v1"], L["o1"], heads, None)
+        got = O.attn_sublayer(h[b:b + 1], None, blk["ln1_g"], blk["ln1_b"], blk["q1"], blk["k1"], blk["v1"], blk["o1"], heads)
+        assert np.abs(got[0] - np.array(ref)).max() <= 1e-12 * np.abs(np.array(ref)).max()
+        ref = _py_attn_sublayer(hb, cb, L["ln2_g"], L["ln2_b"], L["q2"], L["k2"], L["v2"], L["o2"], heads, None)
+        got = O.attn_sublayer(h[b:b + 1], ctx[b:b + 1], blk["ln2_g"], blk["ln2_b"], blk["q2"], blk["k2"], blk["v2"], blk["o2"], heads)
+        assert np.abs(got[0] - np.array(ref)).max() <= 1e-12 * np.abs(np.array(ref)).max()
+        ref = _py_ff_sublayer(hb, L["ln3_g"], L["ln3_b"], L["ff1"], L["ff2"], None)
+        got = O.ff_sublayer(h[b:b + 1], blk["ln3_g"], blk["ln3_b"], blk["ff1"], blk["ff2"])
+        assert np.abs(got[0] - np.array(ref)).max() <= 1e-12 * np.abs(np.array(ref)).max()
+    # the whole block: order self -> cross -> feed-forward
+    got = O.block(h, ctx, blk, heads)
+    ref = np.array(_py_block(h.tolist(), ctx.tolist(), L, heads))
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() <= 1e-12 * scale
+    # every planted mistake moves the reference far away from the oracle: this pin sees them
+    for mut in ("q_from_h", "kv_from_h", "ff_no_ln", "gamma_beta", "cross_first", "no_residual", "gate_first"):
+        bad = np.array(_py_block(h.tolist(), ctx.tolist(), L, heads, mut))
+        assert np.abs(bad - got).max() > 1e-3 * scale, mut
+
+
+def test_block_through_the_stack_wrapper_against_plain_python_loops():
+    # spatial_transformer = proj_in(GroupNorm(x)) -> blocks -> proj_out + x, with the toy block
+    # in the middle (GroupNorm with one channel per group would be degenerate: 2 groups of 2)
+    h, ctx, blk = _toy_block(seed=22)
+    L = _to_lists(blk)
+    r = rng(23)
+    C = 4
+    params = {"gn_g": 1.0 + 0.3 * r.standard_normal(C), "gn_b": 0.2 * r.standard_normal(C),
+              "proj_in": {"W": r.standard_normal((C, C)), "b": r.standard_normal(C)},
+              "proj_out": {"W": r.standard_normal((C, C)), "b": r.standard_normal(C)}, "blocks": [blk, blk]}
+    x = h
+    # GroupNorm by loops: 2 groups of 2 adjacent channels, statistics over the sample's tokens
+    groups, eps = 2, 1e-6
+    xs = x.tolist()
+    hn = []
+    for b in range(2):
+        rows = [[0.0] * C for _ in range(3)]
+        for g in range(groups):
+            vals = [xs[b][t][c] for t in range(3) for c in (2 * g, 2 * g + 1)]
+            mu = sum(vals) / len(vals)
+            var = sum((v - mu) ** 2 for v in vals) / len(vals)
+            for t in range(3):
+                for c in (2 * g, 2 * g + 1):
+                    rows[t][c] = (xs[b][t][c] - mu) / math.sqrt(var + eps) * params["gn_g"][c] + params["gn_b"][c]
+        hn.append(rows)
+    P = {k: {kk: vv.tolist() for kk, vv in params[k].items()} for k in ("proj_in", "proj_out")}
+    hh = [_py_proj(rows, P["proj_in"]) for rows in hn]
+    for _ in range(2):
+        hh = _py_block(hh, ctx.tolist(), L, 2)
+    ref = np.array([[[y + xv for y, xv in zip(yr, xr)] for yr, xr in zip(_py_proj(rows, P["proj_out"]), xb)] for rows, xb in zip(hh, xs)])
+    import oracle.sdxl_block_oracle as OM
+    old = OM.GN_GROUPS
+    try:
+        OM.GN_GROUPS = groups          # the wrapper takes the module's group count
+        got = O.spatial_transformer(x, ctx, params, 2)
+    finally:
+        OM.GN_GROUPS = old
+    assert np.abs(got - ref).max() <= 1e-11 * np.abs(ref).max()
