@@ -707,7 +707,9 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // 4 waves, 48 KB of LDS, three workgroups per CU; larger ones run 128x128 tiles with 8 waves
     // of 32x64, two workgroups per CU.  Down-projections (N = rank <= 64): 64x64 tiles, 5-stage
     // ring.
-    if (maxN <= 64) return launch_cfg<64, 64, 64, 2, 2, 5, false, false>(g, guard, stream);
+    // (a GEGLU group never takes this one: its tiles need the value / gate pairing, which the
+    // 64x128 body below provides for any F)
+    if (maxN <= 64 && !geglu) return launch_cfg<64, 64, 64, 2, 2, 5, false, false>(g, guard, stream);
     // ... except long-K launches (the feed-forward out-projection, K = 4C) that still give every CU
     // a 128x128 tile: over 40 k-steps the operand bytes per FLOP decide, not the ramps
     if (t128 < 1024 && !(maxK >= 2048 && t128 >= 256)) {

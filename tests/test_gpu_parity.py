@@ -132,7 +132,9 @@ def test_lora_linear_layernorm_residual_fp32(B):
     assert np.array_equal(host(resd), host(y))
 
 
-@pytest.mark.parametrize("M,C,F,rank", [(200, 64, 96, 8), (512, 320, 1280, 0), (384, 640, 2560, 64)])
+@pytest.mark.parametrize("M,C,F,rank", [(200, 64, 96, 8), (512, 320, 1280, 0), (384, 640, 2560, 64),
+                                        # narrow outputs (F <= 64: no wider than one down-projection tile)
+                                        (150, 64, 32, 0), (150, 64, 32, 8), (300, 128, 64, 0), (300, 128, 64, 16), (70, 72, 8, 8)])
 def test_lora_linear_geglu_epilogue(B, M, C, F, rank):
     r = rng(M + F)
     p = mkproj(r, 2 * F, C, rank, bias=True, scale=1.0, w_std=0.08)
