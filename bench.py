@@ -66,6 +66,152 @@ def time_events(fn, iters: int):
     return [s.elapsed_time(e) for s, e in zip(starts, ends)]
 
 
+GROUPS = 5     # timed groups of K steps each; the median group is the figure reported
+
+KERNEL_NAMES = {
+    "self_attention": "attention_kernel, latent self-attention",
+    "cross_attention": "attention_kernel, cross-attention to the text tokens",
+    "qkv": "gemm_kernel, grouped q/k/v^T projections (+ the next cross-attention's text k/v)",
+    "attn_out": "gemm_kernel, attention output projection + residual",
+    "cross_q": "gemm_kernel, cross-attention query projection",
+    "ff1": "gemm_kernel, feed-forward in-projection with GEGLU epilogue",
+    "ff2": "gemm_kernel, feed-forward out-projection + residual",
+    "proj_io": "gemm_kernel, proj_in / proj_out",
+    "layernorm": "layernorm_kernel",
+    "groupnorm": "groupnorm_partial_kernel + groupnorm_apply_kernel",
+}
+
+
+class StackLeg:
+    """One stack workload resident on the device: inputs, parameters, workspace, output."""
+
+    def __init__(self, B, G, cfg, seed=0):
+        import torch
+        self.B, self.cfg = B, cfg
+        self.p = G.make_stack_inputs(cfg, seed=seed)
+        self.sp = B.StackParams(self.p)
+        self.x, self.ctx = B.to_bf16(self.p["x"]), B.to_bf16(self.p["ctx"])
+        self.y = torch.empty_like(self.x)
+        self.ws = torch.empty(B.spatial_transformer_workspace_bytes(cfg.Bn, cfg.T, cfg.C, cfg.Tc, cfg.Dc, self.sp.r_max),
+                              dtype=torch.uint8, device="cuda")
+
+    def step(self):
+        self.B.spatial_transformer_fwd(self.x, self.ctx, self.sp, self.cfg.heads, out=self.y, ws=self.ws)
+
+    def param_bytes(self):
+        """bf16 bytes of every parameter tensor of the stack"""
+        n = 0
+        stack = [self.p]
+        while stack:
+            d = stack.pop()
+            for k, v in (d.items() if isinstance(d, dict) else enumerate(d)):
+                if k in ("x", "ctx", "cfg"):
+                    continue
+                if isinstance(v, (dict, list)):
+                    stack.append(v)
+                elif hasattr(v, "size"):
+                    n += int(v.size) * 2
+        return n
+
+
+def time_steps(step_fns, K, W, use_graph):
+    """GROUPS groups of K steps (the step functions taken in turn), each group bracketed by a
+    device synchronisation; returns (median ms per step, every group's ms per step, launch kind).
+    With a graph, one replay runs every step function once."""
+    import torch
+    n = len(step_fns)
+    if use_graph:
+        for f in step_fns:
+            f()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for f in step_fns:
+                f()
+        reps = max(1, K // n)
+
+        def run_group():
+            for _ in range(reps):
+                graph.replay()
+        steps_per_group = reps * n
+    else:
+        def run_group():
+            for i in range(K):
+                step_fns[i % n]()
+        steps_per_group = K
+    for _ in range(max(1, W // n) if use_graph else W):
+        (graph.replay() if use_graph else step_fns[0]())
+    torch.cuda.synchronize()
+    groups = []
+    for _ in range(GROUPS):
+        t0 = time.perf_counter()
+        run_group()
+        torch.cuda.synchronize()
+        groups.append((time.perf_counter() - t0) * 1e3 / steps_per_group)
+    return float(sorted(groups)[len(groups) // 2]), groups, ("hipgraph" if use_graph else "stream")
+
+
+def kernel_table(B, leg, K, ms_per_step):
+    """Per-launch HIP-event durations of every kernel of the stack inside K eager steps."""
+    import numpy as np
+    import torch
+    cfg = leg.cfg
+    d = cfg.depth
+    per_step = {"self_attention": d, "cross_attention": d, "qkv": d, "attn_out": 2 * d, "cross_q": d, "ff1": d, "ff2": d,
+                "proj_io": 2, "layernorm": 3 * d, "groupnorm": 1}
+    M, C, T, Bn, F, r = cfg.M, cfg.C, cfg.T, cfg.Bn, cfg.F, cfg.r
+    rl = r if cfg.lora_ff else 0
+
+    # every projection launch holds its down-projection tiles (x A^T), its base GEMM with the
+    # K segment extended by r, and nothing else; the q/k/v launch also holds the next
+    # cross-attention's text keys / values
+    def proj(m, k, n, rr):
+        return 2.0 * m * k * n + (2.0 * m * k * rr + 2.0 * m * rr * n if rr else 0.0)
+    flop_per_launch = {
+        "self_attention": 4.0 * Bn * T * T * C,
+        "cross_attention": 4.0 * Bn * T * cfg.Tc * C,
+        "qkv": 3 * proj(M, C, C, r) + 2 * proj(Bn * cfg.Tc, cfg.Dc, C, r),
+        "attn_out": proj(M, C, C, r),
+        "cross_q": proj(M, C, C, r),
+        "ff1": proj(M, C, 2 * F, rl),
+        "ff2": proj(M, F, C, rl),
+        "proj_io": proj(M, C, C, 0),
+    }
+    # HBM-bound kernels: algorithmic bytes per launch (LayerNorm: fp32 stream in, bf16 out;
+    # GroupNorm: bf16 in twice (statistics, apply), bf16 out)
+    bytes_per_launch = {"layernorm": 6.0 * M * C, "groupnorm": 6.0 * M * C}
+    B.timing_enable(K * max(per_step.values()) + 8)
+    for _ in range(K):
+        leg.step()
+    torch.cuda.synchronize()
+    kernels = {}
+    for tag, n in per_step.items():
+        dd = B.timing_collect(tag)
+        ms = float(np.mean(dd))
+        e = {"launches": len(dd), "launches_per_step": n, "avg_launch_ms": round(ms, 4), "share_of_step": round(n * ms / ms_per_step, 3)}
+        if tag in flop_per_launch:
+            e["tflops"] = round(flop_per_launch[tag] / (ms * 1e-3) / 1e12, 1)
+            e["frac_of_bf16_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        else:
+            e["gbs"] = round(bytes_per_launch[tag] / (ms * 1e-3) / 1e9, 1)
+        kernels[tag] = e
+    B.timing_disable()
+    tagged = sum(k["share_of_step"] for k in kernels.values())
+    return kernels, per_step, round(tagged, 3)
+
+
+def stack_leg_report(B, leg, K, W, use_graph):
+    cfg = leg.cfg
+    ms, groups, launch = time_steps([leg.step], K, W, use_graph)
+    flops = stack_flops(cfg)
+    tfl = flops / (ms * 1e-3) / 1e12
+    kernels, per_step, tagged = kernel_table(B, leg, min(K, 20), ms)
+    return {"workload": cfg.name, "ms_per_step": round(ms, 4), "group_ms_per_step": [round(g, 4) for g in groups],
+            "gflop_per_step": round(flops / 1e9, 1), "tflops": round(tfl, 2), "frac_of_bf16_peak": round(tfl / PEAK_BF16_TFLOPS, 4),
+            "launch": launch, "kernels": kernels, "tagged_share": tagged,
+            "untagged_share": round(1.0 - tagged, 3)}, per_step
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +219,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-patch", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true", help="skip the legs for the tiny and the 32x32 configuration")
     ap.add_argument("--no-graph", action="store_true", help="launch every step kernel by kernel instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -88,86 +235,23 @@ def main() -> int:
     torch.cuda.set_device(0)
     cfg = G.SDXL64
     K, W = args.steps, args.warmup
+    use_graph = not args.no_graph
 
     # ---------------------------------------------------------------- the stack (metric)
-    p = G.make_stack_inputs(cfg, seed=0)
-    sp = B.StackParams(p)
-    x, ctx = B.to_bf16(p["x"]), B.to_bf16(p["ctx"])
-    y = torch.empty_like(x)
-    ws = torch.empty(B.spatial_transformer_workspace_bytes(cfg.Bn, cfg.T, cfg.C, cfg.Tc, cfg.Dc, sp.r_max), dtype=torch.uint8, device="cuda")
-
-    def step():
-        B.spatial_transformer_fwd(x, ctx, sp, cfg.heads, out=y, ws=ws)
-
     # The library only enqueues kernels on the stream it is given (no allocation, no
     # synchronisation), so one step can be captured once into a HIP graph and replayed: the
     # same launch-overhead removal the paper applies to the base model (Section 4.3).
-    run = step
-    launch = "stream"
-    if not args.no_graph:
-        step()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        run = graph.replay
-        launch = "hipgraph"
-    for _ in range(W):
-        run()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(K):
-        run()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    flops = stack_flops(cfg)
-    tflops = flops / (ms_per_step * 1e-3) / 1e12
-
-    # ---------------- per-kernel durations inside real steps (HIP events, eager launches)
-    # The library records an event pair around each tagged kernel launch on the stream it is
-    # given; K more steps of the same workload run eagerly for this (events cannot be read
-    # back from a replayed graph).
-    per_step = {"self_attention": cfg.depth, "cross_attention": cfg.depth, "qkv": cfg.depth,
-                "attn_out": 2 * cfg.depth, "ff1": cfg.depth, "ff2": cfg.depth}
-    M, C, T, Bn, F, r = cfg.M, cfg.C, cfg.T, cfg.Bn, cfg.F, cfg.r
-    rl = r if cfg.lora_ff else 0
-    # every projection launch holds its down-projection tiles (x A^T), its base GEMM with the
-    # K segment extended by r, and nothing else; the q/k/v launch also holds the next
-    # cross-attention's text keys / values
-    def proj(m, k, n, rr):
-        return 2.0 * m * k * n + (2.0 * m * k * rr + 2.0 * m * rr * n if rr else 0.0)
-    flop_per_launch = {
-        "self_attention": 4.0 * Bn * T * T * C,
-        "cross_attention": 4.0 * Bn * T * cfg.Tc * C,
-        "qkv": 3 * proj(M, C, C, r) + 2 * proj(Bn * cfg.Tc, cfg.Dc, C, r),
-        "attn_out": proj(M, C, C, r),
-        "ff1": proj(M, C, 2 * F, rl),
-        "ff2": proj(M, F, C, rl),
-    }
-    B.timing_enable(K * max(per_step.values()) + 8)
-    for _ in range(K):
-        step()
-    torch.cuda.synchronize()
-    kernels = {}
-    for tag, n in per_step.items():
-        d = B.timing_collect(tag)
-        ms = float(np.mean(d))
-        kernels[tag] = {"launches": len(d), "avg_launch_ms": round(ms, 4),
-                        "tflops": round(flop_per_launch[tag] / (ms * 1e-3) / 1e12, 1),
-                        "share_of_step": round(n * ms / ms_per_step, 3)}
-    B.timing_disable()
-    dom = max(kernels, key=lambda k: kernels[k]["share_of_step"])
-    names = {"self_attention": "attention_kernel, latent self-attention (2 x 10 heads x 4096 x 4096 x 64)",
-             "ff1": "gemm_kernel, feed-forward in-projection with GEGLU epilogue",
-             "ff2": "gemm_kernel, feed-forward out-projection", "qkv": "gemm_kernel, grouped q/k/v^T projections",
-             "attn_out": "gemm_kernel, attention output projection", "cross_attention": "attention_kernel, cross-attention"}
-    roofline = {"kernel": names[dom], "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+    leg = StackLeg(B, G, cfg, seed=0)
+    p = leg.p
+    rep, per_step = stack_leg_report(B, leg, K, W, use_graph)
+    ms_per_step, tflops, kernels, flops = rep["ms_per_step"], rep["tflops"], rep["kernels"], stack_flops(cfg)
+    dom = max((k for k in kernels if "tflops" in kernels[k]), key=lambda k: kernels[k]["share_of_step"])
+    roofline = {"kernel": KERNEL_NAMES[dom], "bound": "mfma", "achieved": kernels[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(kernels[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
-                "traffic": STACK_TRAFFIC_BYTES.get(dom) if cfg is G.SDXL64 else None,
+                "traffic": STACK_TRAFFIC_BYTES.get(dom),
                 "avg_launch_ms": kernels[dom]["avg_launch_ms"], "launches_per_step": per_step[dom],
                 "share_of_step": kernels[dom]["share_of_step"],
-                "measured": "HIP events around every launch of this kernel in %d eager steps" % K}
+                "measured": "HIP events around every launch of this kernel in %d eager steps" % min(K, 20)}
 
     out = {
         "metric": "SDXL transformer-block TFLOP/s (% bf16 MFMA peak); LoRA patch GB/s (% HBM)",
@@ -176,11 +260,49 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": cfg.Bn, "tokens": cfg.T, "channels": cfg.C, "heads": cfg.heads,
                    "blocks": cfg.depth, "lora_rank": cfg.r, "text_ctx": [cfg.Tc, cfg.Dc], "gflop_per_step": round(flops / 1e9, 1),
-                   "launch": launch},
+                   "launch": rep["launch"], "timed": "median of %d groups of %d steps" % (GROUPS, K),
+                   "cache_resident": True,
+                   "cache_note": "weights %.0f MB + workspace %.0f MB < 256 MB last-level cache; see rotated_weights for the leg that is not"
+                                 % (leg.param_bytes() / 1e6, leg.ws.numel() / 1e6)},
+        "group_ms_per_step": rep["group_ms_per_step"],
         "frac_of_bf16_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": roofline,
         "kernels": kernels,
+        "tagged_share": rep["tagged_share"], "untagged_share": rep["untagged_share"],
     }
+
+    # ---------------------- the same step with weights, inputs and workspaces rotated past the cache
+    # In a UNet step the next block's weights are not the ones just used.  Three independent
+    # sets (parameters drawn with other seeds, own workspace and I/O: 3 x ~190 MB > 256 MB) take
+    # turns inside one captured graph, so no set finds its data in the last-level cache.
+    legs = [leg] + [StackLeg(B, G, cfg, seed=s) for s in (1, 2)]
+    rms, rgroups, _ = time_steps([l.step for l in legs], K, W, use_graph)
+    out["rotated_weights"] = {"workload": cfg.name, "sets": len(legs),
+                              "footprint_mb": round(sum(l.ws.numel() + 2 * l.x.numel() * 2 + l.param_bytes() for l in legs) / 1e6, 0),
+                              "ms_per_step": round(rms, 4), "group_ms_per_step": [round(g, 4) for g in rgroups],
+                              "tflops": round(flops / (rms * 1e-3) / 1e12, 2),
+                              "frac_of_bf16_peak": round(flops / (rms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                              "vs_cache_resident": round(rms / ms_per_step, 3)}
+    del legs
+
+    # one step as a replayable graph for the loops below
+    run = leg.step
+    if use_graph:
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            leg.step()
+        run = graph.replay
+
+    # ------------------------------------------- the other stack configurations (report only)
+    other = {}
+    if not args.no_other_configs:
+        for ocfg, oK in ((G.SDXL32, max(5, K // 5)), (G.TINY, K)):
+            oleg = StackLeg(B, G, ocfg, seed=0)
+            orep, _ = stack_leg_report(B, oleg, oK, W, use_graph)
+            orep["steps_per_group"] = oK
+            other[ocfg.name] = (oleg, orep)
+            out.setdefault("other_configs", {})[ocfg.name] = orep
 
     # ------------------------------------------------------------ multi-LoRA projections
     mcfg = G.MULTI_LORA
@@ -382,17 +504,49 @@ def main() -> int:
     del csrc, cdst, cout
 
     # --------------------------------------------------------------------- CPU baseline
+    # The oracle as it stands (numpy in float64, one BLAS matmul per contraction) on the host
+    # cores of this machine, on a bounded sample of each workload.  A baseline only.
     if not args.no_cpu_baseline:
         from oracle import sdxl_block_oracle as O
-        # whole stack calls of the same workload until about 10 s of CPU work are done (at least one)
-        calls, c0 = 0, time.perf_counter()
-        while calls == 0 or (time.perf_counter() - c0 < 10.0 and calls < 8):
-            O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads)
-            calls += 1
-        c1 = time.perf_counter()
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        out["cpu_baseline"] = {"value": round(calls * flops / (c1 - c0) / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-                               "sample": "%d full stack call(s) of the same workload (fp64 numpy oracle), %.1f s" % (calls, c1 - c0)}
+        kind = "oracle (numpy fp64, BLAS)"
+
+        def timed(fn, budget_s, max_calls):
+            calls, c0 = 0, time.perf_counter()
+            while calls == 0 or (time.perf_counter() - c0 < budget_s and calls < max_calls):
+                fn()
+                calls += 1
+            return calls, time.perf_counter() - c0
+
+        calls, dt = timed(lambda: O.spatial_transformer(p["x"], p["ctx"], p, cfg.heads), 8.0, 8)
+        out["cpu_baseline"] = {"value": round(calls * flops / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": kind,
+                               "sample": "%d full stack call(s) of %s, %.1f s" % (calls, cfg.name, dt)}
+        more = {}
+        for name, (oleg, orep) in other.items():
+            ocfg = oleg.cfg
+            calls, dt = timed(lambda: O.spatial_transformer(oleg.p["x"], oleg.p["ctx"], oleg.p, ocfg.heads), 3.0, 3 if ocfg is G.TINY else 1)
+            more[name] = {"value": round(calls * stack_flops(ocfg) / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": kind,
+                          "sample": "%d full stack call(s), %.1f s" % (calls, dt)}
+        # one multi-LoRA projection of the batch (of the four the GPU leg runs)
+        pr = mp["projs"][0]
+        calls, dt = timed(lambda: O.multi_lora_linear(mp["x"], pr["W"], None, pr["A"], pr["B"], pr["scales"], mp["seg_offsets"], mp["seg_adapter"]), 2.0, 3)
+        more[mcfg.name] = {"value": round(calls * (mfl / 4) / dt / 1e12, 4), "unit": "TFLOP/s", "cores": threads, "kind": kind,
+                           "sample": "%d call(s) of one of the 4 projections (32768 rows), %.1f s" % (calls, dt)}
+        # the patch sweep: every tenth matrix of the 310 (31 matrices, all five shapes), patch then unpatch, 3 passes
+        sample = [(14, 1280, 1280), (6, 640, 640), (7, 1280, 2048), (2, 10240, 1280), (2, 1280, 5120)]
+        pm = G.make_patch_inputs(sample, r=G.PATCH_RANK, alpha=G.PATCH_ALPHA, seed=0)
+        pel = sum(d["W"].size for d in pm)
+        pab = sum(d["A"].size + d["B"].size for d in pm)
+
+        def patch_pass():
+            for d in pm:
+                w2, undo = O.lora_patch(d["W"], d["A"], d["B"], d["scale"])
+                O.lora_unpatch(w2, undo)
+        calls, dt = timed(patch_pass, 6.0, 3)
+        more["patch_sweep"] = {"value": round(calls * (pel * 20.0 + pab * 4.0) / dt / 1e9, 2), "unit": "GB/s", "cores": threads, "kind": "oracle (numpy fp32, BLAS)",
+                               "sample": "%d pass(es) of patch + unpatch over every tenth matrix (31 matrices, %.0f M elements; 12 + 8 B per element), %.1f s"
+                                         % (calls, pel / 1e6, dt)}
+        out["cpu_baselines_other_workloads"] = more
     out["context"] = "paper reports up to 7.8x latency / 1.6x throughput for SDXL end to end on H800; no kernel-level figure"
     print(json.dumps(out))
     return 0

@@ -126,7 +126,11 @@ int32_t sd_set_projection_fusion(int32_t on);
 #define SD_TIMING_ATTN_OUT 3         /* attention output projection + residual            */
 #define SD_TIMING_FF1 4              /* feed-forward in-projection with GEGLU epilogue     */
 #define SD_TIMING_FF2 5              /* feed-forward out-projection + residual             */
-#define SD_TIMING_TAGS 6
+#define SD_TIMING_CROSS_Q 6          /* cross-attention query projection                   */
+#define SD_TIMING_PROJ_IO 7          /* the stack's proj_in and proj_out                   */
+#define SD_TIMING_LAYERNORM 8        /* every LayerNorm launch                             */
+#define SD_TIMING_GROUPNORM 9        /* the stack's GroupNorm (partial sums + apply)       */
+#define SD_TIMING_TAGS 10
 int sd_timing_enable(int32_t records_per_tag);
 int sd_timing_collect(int32_t tag, float* ms_host, int32_t capacity, int32_t* count);
 int sd_timing_disable(void);

@@ -444,7 +444,8 @@ class Bal:
         self.close()
 
 
-TIMING_TAGS = {"self_attention": 0, "cross_attention": 1, "qkv": 2, "attn_out": 3, "ff1": 4, "ff2": 5}
+TIMING_TAGS = {"self_attention": 0, "cross_attention": 1, "qkv": 2, "attn_out": 3, "ff1": 4, "ff2": 5,
+               "cross_q": 6, "proj_io": 7, "layernorm": 8, "groupnorm": 9}
 
 
 def timing_enable(records_per_tag: int) -> None:

@@ -161,11 +161,16 @@ struct DepFlags {
 // LayerNorm that also clears the first flag array of the call if that is still due
 static int layernorm(const void* x, int x_f32, const uint16_t* g, const uint16_t* b, float eps, uint16_t* y, int M, int C,
                      hipStream_t stream, DepFlags* dep) {
+    timing_mark(SD_TIMING_LAYERNORM, 0, stream);
+    int rc;
     if (dep && dep->pending && M > 0) {
         dep->pending = false;
-        return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream, dep->f[0], dep->clear_words());
+        rc = launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream, dep->f[0], dep->clear_words());
+    } else {
+        rc = launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream);
     }
-    return launch_layernorm(x, x_f32, g, b, eps, y, M, C, stream);
+    timing_mark(SD_TIMING_LAYERNORM, 1, stream);
+    return rc;
 }
 
 // Run independent projections.  With flags, as one launch: down-projection tiles first, and a
@@ -317,7 +322,7 @@ static int attn_sublayer(const void* x, void* y, int io_f32, const uint16_t* ctx
     } else {
         k_prescaled = push_kv_calls(calls, src, Kkv, Tk, pk, pv, w.k, w.vt, w.tk, w.tv, Bn, C);
     }
-    if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? -1 : SD_TIMING_QKV, dep))) return rc;
+    if ((rc = run_projections(calls.data(), (int)calls.size(), stream, ctx ? SD_TIMING_CROSS_Q : SD_TIMING_QKV, dep))) return rc;
     const int atag = ctx ? SD_TIMING_CROSS_ATTENTION : SD_TIMING_SELF_ATTENTION;
     timing_mark(atag, 0, stream);
     int cut = 0;
@@ -658,10 +663,13 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int M = Bn * T;
     // GroupNorm -> proj_in -> fp32 residual stream h
-    if ((rc = launch_groupnorm(x, sw.g, p->gn_g, p->gn_b, Bn, T, C, 32, 1e-6f, sw.gn, s))) return rc;
+    timing_mark(SD_TIMING_GROUPNORM, 0, s);
+    rc = launch_groupnorm(x, sw.g, p->gn_g, p->gn_b, Bn, T, C, 32, 1e-6f, sw.gn, s);
+    timing_mark(SD_TIMING_GROUPNORM, 1, s);
+    if (rc) return rc;
     ProjCall cin = {sw.g, C, M, C, C, &p->proj_in, sw.f.t1, {sw.h, C, 1, nullptr, 0, false, 0}};
     sw.dep.reset();
-    if ((rc = run_projections(&cin, 1, s, -1, &sw.dep))) return rc;
+    if ((rc = run_projections(&cin, 1, s, SD_TIMING_PROJ_IO, &sw.dep))) return rc;
     for (int i = 0; i < p->depth; ++i) {
         const sd_block_params& b = p->blocks[i];
         // the text keys / values of this block's cross-attention ride in the self-attention launches
@@ -679,7 +687,7 @@ extern "C" int sd_spatial_transformer_fwd(const uint16_t* x, const uint16_t* ctx
     // proj_out + input residual, bf16 out
     if (p->depth == 0 && (rc = launch_cvt_f32_to_bf16(sw.h, sw.g, (size_t)M * C, s))) return rc;
     ProjCall cout = {sw.g, C, M, C, C, &p->proj_out, sw.f.t1, {y, C, 0, x, C, false, 0}};
-    return run_projections(&cout, 1, s, -1, &sw.dep);
+    return run_projections(&cout, 1, s, SD_TIMING_PROJ_IO, &sw.dep);
 }
 
 // ---------------------------------------------------------------------------------------
