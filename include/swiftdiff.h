@@ -168,6 +168,27 @@ int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj* p,
                        int32_t M, int32_t N, int32_t K,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* ---- lora_linear_fwd_static --------------------------------------------------------------
+ * sd_lora_linear_fwd for callers that cannot allocate device memory or carry a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, semantics and bits as sd_lora_linear_fwd without `ws`: the scratch memory (LayerNorm
+ * output, down-projection, dependency flags) is a device array of SD_STATIC_SCRATCH_BYTES built
+ * into the library, which every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing.
+ *   - SD_EWORKSPACE if sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln) exceeds
+ *     SD_STATIC_SCRATCH_BYTES (text names both sizes); use sd_lora_linear_fwd then.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents (each
+ *     call clears the flags it needs itself).  Calls that may overlap on one GPU - different
+ *     streams, concurrent graph launches - race on it: serialise them, or use sd_lora_linear_fwd
+ *     with a workspace each.
+ *   - The first call on a device looks up the array's address on that device (host-side, no
+ *     allocation); make that first call outside graph capture. */
+#define SD_STATIC_SCRATCH_BYTES (16u << 20)
+int sd_lora_linear_fwd_static(const void* x, int32_t x_dtype, const sd_proj* p,
+                              const uint16_t* ln_gamma, const uint16_t* ln_beta, float ln_eps,
+                              const void* residual, void* y, int32_t y_dtype, int32_t epilogue,
+                              int32_t M, int32_t N, int32_t K, void* stream);
+
 /* ---- attn_block_fwd -------------------------------------------------------------------
  * y = x + out( attention( q(LN x), k(src), v(src) ) ),  src = LN x (ctx NULL: latent
  * self-attention) or ctx (cross-attention to the text tokens that guide every denoising

@@ -86,6 +86,7 @@ def _load() -> C.CDLL:
         "sd_ceiling_copy_1r2w_f32": (C.c_int, [vp, vp, vp, sz, vp]),
         "sd_lora_linear_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "sd_lora_linear_fwd": (C.c_int, [vp, i32, P(sd_proj), vp, vp, f32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]),
+        "sd_lora_linear_fwd_static": (C.c_int, [vp, i32, P(sd_proj), vp, vp, f32, vp, vp, i32, i32, i32, i32, i32, vp]),
         "sd_attn_block_workspace_bytes": (sz, [i32, i32, i32, i32, i32, i32]),
         "sd_attn_block_fwd": (C.c_int, [vp, vp, i32, vp, i32, i32, vp, vp, f32, P(sd_proj), P(sd_proj), P(sd_proj), P(sd_proj),
                                         i32, i32, i32, i32, vp, sz, vp]),
@@ -128,7 +129,7 @@ def _load() -> C.CDLL:
 
 _lib = _load()
 EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_set_projection_fusion", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32", "sd_ceiling_copy_1r2w_f32",
-           "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd",
+           "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd", "sd_lora_linear_fwd_static",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_workspace_bytes", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd", "sd_groupnorm_silu_fwd",
            "sd_spatial_transformer_workspace_bytes", "sd_spatial_transformer_fwd",
@@ -245,6 +246,21 @@ def lora_linear_fwd(x: torch.Tensor, p: Proj, ln_gamma=None, ln_beta=None, ln_ep
     w = _ws(need, ws)
     _check(_lib.sd_lora_linear_fwd(_ptr(x), _dt(x), C.byref(p.c), _ptr(ln_gamma), _ptr(ln_beta), ln_eps, _ptr(residual),
                                    _ptr(y), _dt(y), epilogue, M, N, K, _ptr(w), w.numel(), _stream()))
+    return y
+
+
+SD_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def lora_linear_fwd_static(x: torch.Tensor, p: Proj, ln_gamma=None, ln_beta=None, ln_eps: float = 1e-5, residual=None,
+                           out_dtype=torch.bfloat16, epilogue: int = SD_EPI_NONE, out=None) -> torch.Tensor:
+    """sd_lora_linear_fwd_static: no workspace argument.  The call itself allocates nothing when `out` is given."""
+    M, K = x.shape
+    n_rows = p.W.shape[0]
+    N = n_rows // 2 if epilogue == SD_EPI_GEGLU else n_rows
+    y = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=x.device)
+    _check(_lib.sd_lora_linear_fwd_static(_ptr(x), _dt(x), C.byref(p.c), _ptr(ln_gamma), _ptr(ln_beta), ln_eps, _ptr(residual),
+                                          _ptr(y), _dt(y), epilogue, M, N, K, _stream()))
     return y
 
 

@@ -4,6 +4,7 @@
 #include "common.hpp"
 
 #include <string.h>
+#include <mutex>
 #include <vector>
 
 namespace sd {
@@ -211,7 +212,11 @@ static int run_projections(const ProjCall* calls, int n, hipStream_t stream, int
             }
             if (flags > 0 && (rc = dep->clear_now(stream))) return rc;
             int32_t* const base = dep->f[dep->turn];
-            std::vector<int32_t*> slot(n, nullptr);
+            // (no heap for the usual handful of projections: the single-projection entry points allocate nothing)
+            int32_t* slot_small[32] = {nullptr};
+            std::vector<int32_t*> slot_big;
+            if (n > 32) slot_big.assign(n, nullptr);
+            int32_t** const slot = n > 32 ? slot_big.data() : slot_small;
             size_t used = 0;
             for (int i = i0; i < i1; ++i) {
                 if (!flags_of(calls[i])) continue;
@@ -443,40 +448,107 @@ extern "C" size_t sd_lora_linear_workspace_bytes(int32_t M, int32_t N, int32_t K
     return total;
 }
 
-extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
-                                  const uint16_t* ln_beta, float ln_eps, const void* residual, void* y, int32_t y_dtype,
-                                  int32_t epilogue, int32_t M, int32_t N, int32_t K, void* ws, size_t ws_bytes, void* stream) {
-    SD_REQUIRE(M >= 0 && N >= 0, SD_EINVAL, "lora_linear: M=%d N=%d", M, N);
-    int rc = check_proj(p, "lora_linear", K);
-    if (rc) return rc;
-    SD_REQUIRE(x_dtype == SD_BF16 || x_dtype == SD_F32, SD_EINVAL, "lora_linear: x_dtype=%d", x_dtype);
-    SD_REQUIRE(y_dtype == SD_BF16 || y_dtype == SD_F32, SD_EINVAL, "lora_linear: y_dtype=%d", y_dtype);
-    SD_REQUIRE(epilogue == SD_EPI_NONE || epilogue == SD_EPI_GEGLU, SD_EINVAL, "lora_linear: epilogue=%d", epilogue);
-    const bool has_ln = ln_gamma || ln_beta;
-    SD_REQUIRE(!has_ln || (ln_gamma && ln_beta), SD_EINVAL, "lora_linear: LayerNorm needs both gamma and beta");
-    SD_REQUIRE(has_ln || x_dtype == SD_BF16, SD_EINVAL, "lora_linear: fp32 x is only accepted together with a LayerNorm");
-    SD_REQUIRE(!(epilogue == SD_EPI_GEGLU && residual), SD_EINVAL, "lora_linear: GEGLU epilogue takes no residual");
-    if (M == 0 || N == 0) return SD_OK;
-    SD_REQUIRE(x && y, SD_EINVAL, "lora_linear: x or y is null");
-    SD_REQUIRE(aligned16(x) && aligned16(y) && aligned16(residual) && aligned16(p->bias), SD_EINVAL,
-               "lora_linear: pointers must be 16-byte aligned");
-    SD_REQUIRE(ws_bytes >= sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln) && ws, SD_EWORKSPACE,
-               "lora_linear: workspace of %zu bytes, need %zu", ws_bytes, sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln));
+static int lora_linear_impl(const char* who, const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
+                            const uint16_t* ln_beta, float ln_eps, const void* residual, void* y, int32_t y_dtype,
+                            int32_t epilogue, int32_t M, int32_t N, int32_t K, void* ws, size_t ws_bytes, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool has_ln = ln_gamma || ln_beta;
     Workspace w(ws, ws_bytes);
     const uint16_t* xin = static_cast<const uint16_t*>(x);
     uint16_t* n = has_ln ? (uint16_t*)w.take((size_t)M * K * 2) : nullptr;
     uint16_t* t = (uint16_t*)w.take((size_t)M * (p->r > 0 ? p->r : 8) * 2);
     DepFlags dep;
     if (p->r > 0) dep.carve(w, M);
-    SD_REQUIRE(w.ok(), SD_EWORKSPACE, "lora_linear: workspace too small");
+    SD_REQUIRE(w.ok(), SD_EWORKSPACE, "%s: workspace too small", who);
     dep.reset();
+    int rc;
     if (has_ln) {
         if ((rc = layernorm(x, x_dtype == SD_F32, ln_gamma, ln_beta, ln_eps, n, M, K, s, &dep))) return rc;
         xin = n;
     }
     ProjCall c = {xin, K, M, K, N, p, t, {y, N, y_dtype == SD_F32, residual, N, false, epilogue == SD_EPI_GEGLU ? N : 0}};
     return run_projections(&c, 1, s, -1, &dep);
+}
+
+// argument checks shared by the two entry points; *empty: nothing to do
+static int lora_linear_check(const char* who, const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
+                             const uint16_t* ln_beta, const void* residual, void* y, int32_t y_dtype, int32_t epilogue, int32_t M,
+                             int32_t N, int32_t K, bool* empty) {
+    *empty = false;
+    SD_REQUIRE(M >= 0 && N >= 0, SD_EINVAL, "%s: M=%d N=%d", who, M, N);
+    int rc = check_proj(p, who, K);
+    if (rc) return rc;
+    SD_REQUIRE(x_dtype == SD_BF16 || x_dtype == SD_F32, SD_EINVAL, "%s: x_dtype=%d", who, x_dtype);
+    SD_REQUIRE(y_dtype == SD_BF16 || y_dtype == SD_F32, SD_EINVAL, "%s: y_dtype=%d", who, y_dtype);
+    SD_REQUIRE(epilogue == SD_EPI_NONE || epilogue == SD_EPI_GEGLU, SD_EINVAL, "%s: epilogue=%d", who, epilogue);
+    const bool has_ln = ln_gamma || ln_beta;
+    SD_REQUIRE(!has_ln || (ln_gamma && ln_beta), SD_EINVAL, "%s: LayerNorm needs both gamma and beta", who);
+    SD_REQUIRE(has_ln || x_dtype == SD_BF16, SD_EINVAL, "%s: fp32 x is only accepted together with a LayerNorm", who);
+    SD_REQUIRE(!(epilogue == SD_EPI_GEGLU && residual), SD_EINVAL, "%s: GEGLU epilogue takes no residual", who);
+    if (M == 0 || N == 0) { *empty = true; return SD_OK; }
+    SD_REQUIRE(x && y, SD_EINVAL, "%s: x or y is null", who);
+    SD_REQUIRE(aligned16(x) && aligned16(y) && aligned16(residual) && aligned16(p->bias), SD_EINVAL,
+               "%s: pointers must be 16-byte aligned", who);
+    return SD_OK;
+}
+
+extern "C" int sd_lora_linear_fwd(const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
+                                  const uint16_t* ln_beta, float ln_eps, const void* residual, void* y, int32_t y_dtype,
+                                  int32_t epilogue, int32_t M, int32_t N, int32_t K, void* ws, size_t ws_bytes, void* stream) {
+    bool empty;
+    int rc = lora_linear_check("lora_linear", x, x_dtype, p, ln_gamma, ln_beta, residual, y, y_dtype, epilogue, M, N, K, &empty);
+    if (rc || empty) return rc;
+    const bool has_ln = ln_gamma || ln_beta;
+    SD_REQUIRE(ws_bytes >= sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln) && ws, SD_EWORKSPACE,
+               "lora_linear: workspace of %zu bytes, need %zu", ws_bytes, sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln));
+    return lora_linear_impl("lora_linear", x, x_dtype, p, ln_gamma, ln_beta, ln_eps, residual, y, y_dtype, epilogue, M, N, K, ws, ws_bytes, stream);
+}
+
+// ---------------------------------------------------------------------------------------
+// lora_linear_fwd_static: the same call for callers that cannot allocate a workspace
+// ---------------------------------------------------------------------------------------
+// The scratch memory of sd_lora_linear_fwd (LayerNorm output, down-projection, dependency
+// flags) in a device array of the library itself.  Every GPU the library runs on holds its
+// own copy, at its own address, until the process ends.  The name below is a host-side
+// stand-in: only the address hipGetSymbolAddress returns may be handed to kernels.
+namespace sd {
+static __device__ __align__(256) unsigned char scratch[SD_STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device, looked up once per device
+static int static_scratch(void** out) {
+    int dev = -1;
+    SD_HIP_CHECK(hipGetDevice(&dev));
+    SD_REQUIRE(dev >= 0 && dev < MAX_DEVICES, SD_EUNSUPPORTED, "lora_linear_static: device %d", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        SD_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        SD_REQUIRE(ptr && (reinterpret_cast<uintptr_t>(ptr) & 255u) == 0, SD_EHIP, "lora_linear_static: scratch array at %p", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SD_OK;
+}
+}  // namespace sd
+
+extern "C" int sd_lora_linear_fwd_static(const void* x, int32_t x_dtype, const sd_proj* p, const uint16_t* ln_gamma,
+                                         const uint16_t* ln_beta, float ln_eps, const void* residual, void* y, int32_t y_dtype,
+                                         int32_t epilogue, int32_t M, int32_t N, int32_t K, void* stream) {
+    bool empty;
+    int rc = lora_linear_check("lora_linear_static", x, x_dtype, p, ln_gamma, ln_beta, residual, y, y_dtype, epilogue, M, N, K, &empty);
+    if (rc || empty) return rc;
+    const bool has_ln = ln_gamma || ln_beta;
+    const size_t need = sd_lora_linear_workspace_bytes(M, N, K, p->r, has_ln);
+    SD_REQUIRE(need <= (size_t)SD_STATIC_SCRATCH_BYTES, SD_EWORKSPACE,
+               "lora_linear_static: M=%d K=%d r=%d%s needs %zu bytes of scratch, the built-in array holds %zu: use sd_lora_linear_fwd with a workspace",
+               M, K, p->r, has_ln ? " with LayerNorm" : "", need, (size_t)SD_STATIC_SCRATCH_BYTES);
+    void* ptr = nullptr;
+    if ((rc = static_scratch(&ptr))) return rc;
+    return lora_linear_impl("lora_linear_static", x, x_dtype, p, ln_gamma, ln_beta, ln_eps, residual, y, y_dtype, epilogue, M, N, K, ptr,
+                            SD_STATIC_SCRATCH_BYTES, stream);
 }
 
 // ---------------------------------------------------------------------------------------
