@@ -148,6 +148,24 @@ def test_lora_linear_geglu_epilogue(B, M, C, F, rank):
     assert rel_err(O.geglu(np.concatenate([u[:, F:], u[:, :F]], 1)), ref) > 10 * BF16_TOL
 
 
+def test_lora_linear_geglu_large_ragged(B):
+    """Enough tiles for the 256-row GEGLU tile body (two rounds of the chip or more), with a
+    ragged last row tile, a ragged last column tile and a K that is not a multiple of 64."""
+    M, C, F, rank = 8192 + 77, 328, 2560 + 8, 16
+    r = rng(8269)
+    p = mkproj(r, 2 * F, C, rank, bias=True, scale=0.5, w_std=0.08)
+    x = G.bf16_round(r.standard_normal((M, C)).astype(np.float32))
+    ref = O.geglu(O.lora_linear(x, p["W"], p["b"], p["A"], p["B"], p["scale"]))
+    y = B.lora_linear_fwd(dev(x, B), B.Proj.from_numpy(p), epilogue=B.SD_EPI_GEGLU)
+    got = host(y)
+    assert got.shape == (M, F)
+    assert rel_err(got, ref) <= BF16_TOL
+    # the corners too, each on its own scale
+    for rows, cols in ((slice(0, 256), slice(0, 128)), (slice(M - 77, M), slice(F - 8, F)), (slice(M - 77, M), slice(0, 128))):
+        assert rel_err(got[rows, cols], ref[rows, cols]) <= BF16_TOL
+    assert B.gemm_dep_timeouts() == 0
+
+
 # ---------------------------------------------------------------------- attention_fwd
 def vt_layout(v, B):
     """[Bn, Tk, C] -> the transposed, per-sample padded layout [C, Bn * Tkp]."""
@@ -684,3 +702,55 @@ def test_zz_no_tile_gave_up_waiting(B):
     """Runs last in this file: across everything above, no base-GEMM tile ran out of spins
     while waiting for a down-projection tile of its own launch."""
     assert B.gemm_dep_timeouts() == 0
+
+
+@pytest.mark.parametrize("boost", [1.0, 4.0])
+def test_attn_block_scores_that_climb_from_key_tile_to_key_tile(B, boost):
+    """Inside the block the attention kernel first tries without measuring the maximum of the
+    key tiles between a segment's first and last: the exponentials are formed against the first
+    tile's maximum, which is exact as long as nothing overflows, and a workgroup whose row sums
+    or accumulators end up non-finite runs again in the measured form.  Cross-attention with keys
+    under the caller's control (W_k picks the context's leading channels): the scores of
+    successive 64-key tiles step up, fall back, stay level and step up again.  boost = 1: the
+    steps (up to 2^68 above the first tile) stay in range, the first attempt stands.  boost = 4:
+    they reach 2^270, the first attempt overflows and the measured form must take over.  Half of
+    the queries see the mirrored, falling sequence, so both kinds share wavefronts.  Ragged last
+    tile."""
+    import torch
+    Bn, T, Tc, C, Dc = 2, 200, 64 * 6 + 23, 64, 64
+    r = rng(4242)
+    n0 = r.standard_normal(C).astype(np.float32)
+    n0 = (n0 - n0.mean()) / n0.std()                       # what LayerNorm makes of a row along n0
+    sign = np.where(r.random((Bn, T, 1)) < 0.5, 1.0, -1.0).astype(np.float32)
+    h = (sign * n0 * (1.0 + 0.05 * r.standard_normal((Bn, T, 1))) + 0.15 * r.standard_normal((Bn, T, C))).astype(np.float32)
+    # natural-log score of key j for a query along +n0: level[j // 64] (+ noise); the head-room is 8 in log2 = 5.5
+    level = boost * np.array([0.0, 14.0, 3.0, 3.5, 30.0, 29.0, 47.0], np.float32)
+    a = level[np.arange(Tc) // 64] + 0.5 * r.standard_normal(Tc).astype(np.float32)
+    ctx = np.zeros((Bn, Tc, Dc), np.float32)
+    ctx[:, :, :C] = (a[None, :, None] * n0[None, None, :] / C * 8.0)
+    ctx += 0.05 * r.standard_normal(ctx.shape).astype(np.float32)
+    ctx = G.bf16_round(ctx)
+    eye = np.eye(C, dtype=np.float32)
+    mk = lambda W, bias: {"W": G.bf16_round(W), "b": bias, "A": G.bf16_round(0.05 * r.standard_normal((8, W.shape[1])).astype(np.float32)),
+                          "B": G.bf16_round(0.02 * r.standard_normal((W.shape[0], 8)).astype(np.float32)), "scale": 0.5}
+    pq, pk = mk(eye, None), mk(eye, None)
+    pv = mk(0.3 * r.standard_normal((C, Dc)).astype(np.float32), None)
+    po = mk(0.3 * r.standard_normal((C, C)).astype(np.float32), G.bf16_round(0.1 * r.standard_normal(C).astype(np.float32)))
+    g, b = np.ones(C, np.float32), np.zeros(C, np.float32)
+    ref = O.attn_sublayer(h, ctx, g, b, pq, pk, pv, po, 1)
+    # the test is what it says: scores (in powers of two) of a +n0 query climb from tile to tile, past 2^100 with the boost
+    qn = O.proj(O.layernorm(h, g, b), pq)
+    kn = O.proj(ctx, pk)
+    i_pos = int(np.argmax(sign[0, :, 0] > 0))
+    s_row = (qn[0, i_pos] @ kn[0].T) / 8.0 * 1.4426950408889634
+    tile_max = [s_row[i:i + 64].max() for i in range(0, Tc, 64)]
+    assert tile_max[1] - tile_max[0] > 8 and tile_max[2] < tile_max[1] and tile_max[4] - tile_max[3] > 8 and tile_max[6] - tile_max[5] > 8
+    assert (tile_max[6] - tile_max[0] > 140) == (boost > 1) and tile_max[6] - tile_max[0] < (300 if boost > 1 else 100)
+    y = B.attn_block_fwd(torch.from_numpy(h).cuda(), dev(ctx, B), dev(g, B), dev(b, B), B.Proj.from_numpy(pq), B.Proj.from_numpy(pk),
+                         B.Proj.from_numpy(pv), B.Proj.from_numpy(po), 1)
+    got = host(y)
+    assert np.isfinite(got).all()
+    assert rel_err(got - h, ref - h) <= BF16_TOL
+    # negative control: the output depends on which keys win (attention to the first tile only is far away)
+    ref_first = O.attn_sublayer(h, ctx[:, :64], g, b, pq, pk, pv, po, 1)
+    assert rel_err(ref_first - h, ref - h) > 10 * BF16_TOL
