@@ -100,11 +100,21 @@ typedef struct sd_patch_multi_desc {
 
 const char* sd_last_error(void);
 int32_t sd_version(void);
-/* Self-check of the projection launches (Section 2's LoRA projection as one launch: tiles of
- * the base GEMM wait, behind a bounded spin, for the down-projection tiles of the same launch):
- * *count receives how many tiles, since the library was loaded, ran out of spins.  Always 0
- * unless that protocol is broken, in which case outputs were wrong.  count: host.
- * Synchronises the device. */
+/* Self-check of the projection launches.  Section 2's LoRA projection runs as one launch: the
+ * tiles of the down-projection t = scale * x A^T come first in the grid, and a tile of the base
+ * GEMM waits, behind a bounded spin, for the rows of t it reads.
+ *   Forward progress rests on two things: (i) the down-projection tiles are the lowest-numbered
+ *   workgroups of the launch and the hardware dispatches workgroups in index order on every XCD,
+ *   so each of them is running or done before any tile can wait for it, and they wait for
+ *   nothing; (ii) a workspace serves one call at a time (its flags are per call).  HIP does not
+ *   promise (i) in writing; the spin is bounded (2^19 polls, about half a second) so that every wavefront
+ *   exits even if it should not hold.
+ *   A tile that runs out of spins writes NaN to its whole output tile, so the damage is visible in
+ *   the data of that call and of everything computed from it; the forward call itself has long
+ *   returned SD_OK by then (calls only enqueue).  *count receives how many tiles, since the library
+ *   was loaded, ran out of spins: 0 unless the protocol is broken.
+ *   count: host.  This call synchronises the device: a serving loop polls it once per request,
+ *   after the request's last step, not per step. */
 int sd_gemm_dep_timeouts(int64_t* count);
 /* Diagnostic switch for the same: on = 0 makes every later call run a projection as two
  * launches (all down-projections, then all base GEMMs) instead of one, and merge the halves
@@ -207,6 +217,8 @@ int sd_attn_block_fwd(const void* x, void* y, int32_t io_dtype,
                       void* ws, size_t ws_bytes, void* stream);
 
 /* ---- attention_fwd (helper) -----------------------------------------------------------
+ * The attention operator of the base model's transformer blocks (Section 4.3, "Kernel-level
+ * optimizations" names it among the operators worth a kernel of their own), on its own:
  * out[b, t, h*64 + d] = softmax_k(q[b,t,h,:] . k[b,k,h,:] / 8) v[b,k,h,d]
  *   q   device [Bn, Tq, C] bf16;  k device [Bn, Tk, C] bf16
  *   vt  device [C, Bn * Tkp] bf16: V transposed, sample b's keys at columns
@@ -222,6 +234,8 @@ int sd_attention_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* vt, u
                      void* ws, size_t ws_bytes, void* stream);
 
 /* ---- ff_block_fwd (helper) ------------------------------------------------------------
+ * The block's feed-forward sub-layer with the GEGLU of Section 4.3 ("Kernel-level optimizations":
+ * GELU and the matrix multiplication as one operator) in the first projection's epilogue:
  * y = x + ff2( geglu( ff1( LN x ) ) );  ff1: [2F, C] with bias, ff2: [C, F] with bias. */
 size_t sd_ff_block_workspace_bytes(int32_t M, int32_t C, int32_t F, int32_t r_max);
 int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype,
@@ -230,7 +244,8 @@ int sd_ff_block_fwd(const void* x, void* y, int32_t io_dtype,
                     void* ws, size_t ws_bytes, void* stream);
 
 /* ---- groupnorm_fwd (helper) -----------------------------------------------------------
- * Token-major GroupNorm: x, y device [Bn, T, C] bf16; statistics per (sample, group of
+ * The GroupNorm that precedes the transformer blocks (Section 4.3, "Kernel-level optimizations"
+ * lists GroupNorm among the base model's operators), token-major: x, y device [Bn, T, C] bf16; statistics per (sample, group of
  * C/groups adjacent channels) over all tokens, biased variance, per-channel affine. */
 size_t sd_groupnorm_workspace_bytes(int32_t Bn, int32_t T, int32_t C, int32_t groups);
 int sd_groupnorm_fwd(const uint16_t* x, uint16_t* y, const uint16_t* gamma, const uint16_t* beta,
@@ -284,7 +299,10 @@ int sd_multi_lora_linear_fwd(const uint16_t* x, const uint16_t* W, const uint16_
  *   sd_lora_patch(plan_dev, n, tiles, stream)     one grouped launch over all matrices
  *   sd_lora_unpatch(plan_dev, n, tiles, stream)   W <- undo, bit-exact
  * Calling unpatch without a preceding patch on the same undo buffers copies whatever the
- * buffers hold; the library cannot detect that.  Ordering against kernels that read W on
+ * buffers hold; the library cannot detect that.  Nor can it detect a second patch without an
+ * unpatch in between: that one overwrites `undo` with already-patched bits and the base weights
+ * are lost (stack two adapters with sd_lora_patch_multi instead, or give the second patch its
+ * own undo buffers and unpatch in reverse order).  Ordering against kernels that read W on
  * other streams is the caller's job (events). */
 size_t sd_patch_plan_bytes(int32_t n);
 int sd_patch_plan_build(const sd_patch_desc* descs, int32_t n, void* plan_host, size_t plan_bytes,

@@ -49,16 +49,25 @@ extern "C" int sd_bal_start(sd_bal* b) {
     SD_REQUIRE(!b->started, SD_EINVAL, "bal_start: already started");
     b->started = true;
     b->t_start = std::chrono::steady_clock::now();
+    auto finished = [b](bool ok) {
+        std::lock_guard<std::mutex> lk(b->mu);
+        if (!ok) ++b->failed;
+        if (++b->done == b->n)
+            b->load_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - b->t_start).count();
+        b->cv.notify_all();
+    };
+    int not_started = 0;
     for (int i = 0; i < b->n; ++i) {
-        b->loaders.emplace_back([b, i] {
-            const int rc = b->load(b->user, i);
-            std::lock_guard<std::mutex> lk(b->mu);
-            if (rc != 0) ++b->failed;
-            if (++b->done == b->n)
-                b->load_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - b->t_start).count();
-            b->cv.notify_all();
-        });
+        // nothing may propagate out of an extern "C" function: an adapter whose thread cannot be
+        // created counts as a failed, finished load, so the handle still reaches done == n
+        try {
+            b->loaders.emplace_back([b, i, finished] { finished(b->load(b->user, i) == 0); });
+        } catch (...) {
+            finished(false);
+            ++not_started;
+        }
     }
+    SD_REQUIRE(not_started == 0, SD_ELOAD, "bal_start: %d of %d loader threads could not be created", not_started, b->n);
     return SD_OK;
 }
 

@@ -216,6 +216,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
     // (GUARD only) takes per-lane 64-bit addresses so that chunks past the segment's end can
     // point at the zero page.
     bool dep_ready = wflag == nullptr;
+    bool timed_out = false;      // this wavefront gave up waiting: its output is poisoned below
     auto issue_tile = [&](int t, int stg) {
         const bool s1 = t >= nk0;
         const int kb = (s1 ? t - nk0 : t) * BK;
@@ -232,6 +233,7 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
                 if (__all(v >= P.wait_need)) break;
                 if (spins >= DEP_SPIN_LIMIT) {
                     if (tid == 0) atomicAdd(&g_gemm_dep_timeouts, 1ull);
+                    timed_out = true;
                     break;
                 }
                 __builtin_amdgcn_s_sleep(8);
@@ -390,7 +392,9 @@ __device__ __forceinline__ void gemm_tile(const GemmProblem& P, const int tile, 
 
     // ---- epilogue
     float* stage = reinterpret_cast<float*>(lds) + wave * 32 * EPI_STRIDE;
-    const float alpha = P.alpha;
+    // a wavefront that read its second K segment without the producer's flag stores NaN: what it
+    // computed from a stale or half-written down-projection must not look like a result
+    const float alpha = timed_out ? __builtin_nanf("") : P.alpha;
     int32_t* const sig = P.signal;
     // a tile that lies inside the output with 16-byte-aligned rows takes straight-line code: all
     // staged pieces read, then all residual pieces, then all stores (no per-lane bounds)

@@ -225,7 +225,199 @@ __device__ __forceinline__ int find_entry_multi(const PatchMultiEntry* __restric
 // the adapters are applied one after the other, W_i = fl32(W_{i-1} + fl32(scale_i * (B_i A_i))),
 // so the result equals successive single patches bit for bit at one third of their traffic for
 // two adapters.  Optionally also writes the bf16 copy of W' that the bf16 GEMMs read.
-__global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const PatchMultiEntry* __restrict__ plan, int n) {
+//
+// CB: 32-column MFMA blocks per wavefront, interleaved so that lane l holds CB adjacent columns
+// (c0 + CB * (l % 32) + {0 .. CB-1}) of 16 rows.  A workgroup covers 32 rows x 256 columns with
+// 8 / CB wavefronts.  The second adapter doubles the matrix-core time of a tile (64 fp32 MFMAs of
+// 64 clocks per adapter and 32 x 128 elements) while its traffic stays the same, and a wavefront
+// that multiplies has nothing in flight.  CB = 2 keeps a tile in half the registers (W 32,
+// accumulators 32), so four wavefronts fit a SIMD instead of two: measured 15 % slower on the
+// 310-matrix sweep (8-byte accesses, more streams per channel), so CB = 4 is what is launched; what
+// did help is the pipelined path below.
+template <int CB>
+struct PatchVec;
+template <>
+struct PatchVec<4> { typedef float4 type; };
+template <>
+struct PatchVec<2> { typedef float2 type; };
+template <int CB>
+__device__ __forceinline__ float& pv_at(typename PatchVec<CB>::type& v, int j) { return reinterpret_cast<float*>(&v)[j]; }
+
+template <int CB>
+__device__ __forceinline__ typename PatchVec<CB>::type nt_loadv(const float* p) {
+    typedef float nt_vec __attribute__((ext_vector_type(CB)));
+    nt_vec t = __builtin_nontemporal_load(reinterpret_cast<const nt_vec*>(p));
+    typename PatchVec<CB>::type r;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) reinterpret_cast<float*>(&r)[j] = t[j];
+    return r;
+}
+template <int CB>
+__device__ __forceinline__ void nt_storev(float* p, const typename PatchVec<CB>::type& v) {
+    typedef float nt_vec __attribute__((ext_vector_type(CB)));
+    nt_vec t;
+#pragma unroll
+    for (int j = 0; j < CB; ++j) t[j] = reinterpret_cast<const float*>(&v)[j];
+    __builtin_nontemporal_store(t, reinterpret_cast<nt_vec*>(p));
+}
+
+// delta_full for CB column blocks: acc[j][v] += sum_k B[row(v)][k] * A[k][col + j]
+template <int CB>
+__device__ __forceinline__ void delta_full_cb(const float* __restrict__ A, const float* __restrict__ B, int r, int in, int r0,
+                                              int col, int l32, int hi, f32x16 (&acc)[CB]) {
+    typedef typename PatchVec<CB>::type vec;
+    const float* bp = B + (size_t)(r0 + l32) * r + hi;
+    const float* ap = A + (size_t)hi * in + col;
+    const int kp_n = r >> 1;
+    int kp0 = 0;
+    // batches of FRAG_KP k pairs: fragments requested together, their MFMAs behind them
+#pragma unroll 1
+    for (; kp0 + FRAG_KP <= kp_n; kp0 += FRAG_KP) {
+        float bv[FRAG_KP];
+        vec av[FRAG_KP];
+#pragma unroll
+        for (int kp = 0; kp < FRAG_KP; ++kp) bv[kp] = bp[2 * (kp0 + kp)];
+#pragma unroll
+        for (int kp = 0; kp < FRAG_KP; ++kp) av[kp] = *reinterpret_cast<const vec*>(ap + (size_t)(2 * (kp0 + kp)) * in);
+#pragma unroll
+        for (int kp = 0; kp < FRAG_KP; ++kp)
+#pragma unroll
+            for (int j = 0; j < CB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv[kp], pv_at<CB>(av[kp], j), acc[j], 0, 0, 0);
+    }
+#pragma unroll 1
+    for (; kp0 < kp_n; ++kp0) {
+        const float bv = bp[2 * kp0];
+        vec av = *reinterpret_cast<const vec*>(ap + (size_t)(2 * kp0) * in);
+#pragma unroll
+        for (int j = 0; j < CB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, pv_at<CB>(av, j), acc[j], 0, 0, 0);
+    }
+    if (r & 1) {   // odd rank: last k with a zero partner
+        const int kk = r - 1;
+        const float bv = hi ? 0.f : B[(size_t)(r0 + l32) * r + kk];
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const float a = hi ? 0.f : A[(size_t)kk * in + col + j];
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, a, acc[j], 0, 0, 0);
+        }
+    }
+}
+
+template <int CB>
+__device__ __forceinline__ void delta_ragged_cb(const float* __restrict__ A, const float* __restrict__ B, int r, int out, int in,
+                                                int r0, int col, int l32, int hi, f32x16 (&acc)[CB]) {
+    const int brow = r0 + l32;
+    const int kp_n = (r + 1) >> 1;
+#pragma unroll 1
+    for (int kp = 0; kp < kp_n; ++kp) {
+        const int kk = 2 * kp + hi;
+        const bool kv = kk < r;
+        const float bv = (kv && brow < out) ? B[(size_t)brow * r + kk] : 0.f;
+#pragma unroll
+        for (int j = 0; j < CB; ++j) {
+            const float a = (kv && col + j < in) ? A[(size_t)kk * in + col + j] : 0.f;
+            acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(bv, a, acc[j], 0, 0, 0);
+        }
+    }
+}
+
+// A full tile under NA adapters of rank 32, the common case, as one straight line.  What a
+// wavefront spends per tile is a chain of round trips: with the fragments of a batch requested
+// only after the MFMAs of the batch before have been issued (a wavefront issues its 32x32x2 fp32
+// MFMAs one per 64 clocks, in order), every batch pays an L2 round trip on top of its matrix
+// time, and a second adapter adds all of its own.  Here the k pairs form units of PIPE_KP, the
+// fragments of unit u + PIPE_DEPTH are requested before the MFMAs of unit u, across adapter
+// boundaries, and the first units are requested ahead of the W tile itself.  Same MFMAs in the
+// same order on the same operands as the plain loop: same bits.
+// (measured on the 310-matrix sweep with two adapters: 2.77 ms with the plain loop, 2.55 ms with
+// units of 4 k pairs two units ahead; three units ahead spills and loses; where W's undo stores
+// sit among the first units makes no difference)
+constexpr int PIPE_KP = 4, PIPE_DEPTH = 2;
+template <int NA>
+__device__ __forceinline__ void patch_tile_rank32(const PatchMultiEntry& E, int in, int r0, int col, int l32, int hi) {
+    constexpr int UPA = 16 / PIPE_KP;            // units per adapter
+    constexpr int U = NA * UPA, SLOTS = PIPE_DEPTH + 1;
+    float* __restrict__ W = E.d.W;
+    float* __restrict__ Und = E.d.undo;
+    uint16_t* __restrict__ S = E.d.serving;
+    float bvb[SLOTS][PIPE_KP];
+    float4 avb[SLOTS][PIPE_KP];
+    // addresses as a wave-uniform base (adapter, k pair: scalar arithmetic) plus one 32-bit byte
+    // offset per lane for all of B's fragments and one for all of A's
+    const uint32_t boff = (uint32_t)(((r0 + l32) * 32 + hi) * 4);
+    const uint32_t aoff = (uint32_t)(((size_t)hi * in + col) * 4);
+    auto issue = [&](int u, int slot) {
+        const int a = u / UPA, k0 = (u % UPA) * PIPE_KP;
+        const char* bbase = reinterpret_cast<const char*>(E.d.B[a]);
+        const char* abase = reinterpret_cast<const char*>(E.d.A[a]);
+#pragma unroll
+        for (int kp = 0; kp < PIPE_KP; ++kp) bvb[slot][kp] = *reinterpret_cast<const float*>(bbase + 8 * (k0 + kp) + boff);
+#pragma unroll
+        for (int kp = 0; kp < PIPE_KP; ++kp)
+            avb[slot][kp] = *reinterpret_cast<const float4*>(abase + (size_t)(2 * (k0 + kp)) * in * 4 + aoff);
+    };
+#pragma unroll
+    for (int u = 0; u < PIPE_DEPTH && u < U; ++u) issue(u, u);
+    // W, undo and serving addresses likewise: the row of register v lies d(v) = 8 * (v / 4) + v % 4
+    // rows below the lane's first, a wave-uniform distance; one 32-bit byte offset per lane serves
+    // all three arrays (the caller checked that the matrix has fewer than 2^30 elements)
+    const uint32_t woff = (uint32_t)(((size_t)(r0 + 4 * hi) * in + col) * 4);
+    auto row_bytes = [&](int v) -> size_t { return (size_t)(8 * (v >> 2) + (v & 3)) * in * 4; };
+    float4 w[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w[v] = NT_LOAD4(reinterpret_cast<const float*>(reinterpret_cast<const char*>(W) + row_bytes(v) + woff));
+    // W's old bits go out first, as one burst of stores, before any adapter's product
+#pragma unroll
+    for (int v = 0; v < 16; ++v) NT_STORE4(reinterpret_cast<float*>(reinterpret_cast<char*>(Und) + row_bytes(v) + woff), w[v]);
+    f32x16 acc[4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (u % UPA == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+        }
+        // (the scheduler is kept from hoisting every unit's requests to the top, which would need
+        // registers for all of them at once)
+        __builtin_amdgcn_sched_barrier(0);
+        if (u + PIPE_DEPTH < U) issue(u + PIPE_DEPTH, (u + PIPE_DEPTH) % SLOTS);
+        __builtin_amdgcn_sched_barrier(0);
+        const int slot = u % SLOTS;
+#pragma unroll
+        for (int kp = 0; kp < PIPE_KP; ++kp) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(bvb[slot][kp], avb[slot][kp].x, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(bvb[slot][kp], avb[slot][kp].y, acc[1], 0, 0, 0);
+            acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(bvb[slot][kp], avb[slot][kp].z, acc[2], 0, 0, 0);
+            acc[3] = __builtin_amdgcn_mfma_f32_32x32x2f32(bvb[slot][kp], avb[slot][kp].w, acc[3], 0, 0, 0);
+        }
+        if (u % UPA == UPA - 1) {
+            const float scale = E.d.scale[u / UPA];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                w[v].x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
+                w[v].y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
+                w[v].z = __fadd_rn(w[v].z, __fmul_rn(scale, acc[2][v]));
+                w[v].w = __fadd_rn(w[v].w, __fmul_rn(scale, acc[3][v]));
+            }
+        }
+    }
+    // (the offset is laundered so that the sixteen row addresses are formed again here instead of
+    // being carried, or spilled, through the adapters' products)
+    uint32_t woff2 = woff;
+    asm volatile("" : "+v"(woff2));
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        NT_STORE4(reinterpret_cast<float*>(reinterpret_cast<char*>(W) + row_bytes(v) + woff2), w[v]);
+        if (S) {
+            bf16x4 o = {(__bf16)w[v].x, (__bf16)w[v].y, (__bf16)w[v].z, (__bf16)w[v].w};
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<char*>(S) + row_bytes(v) / 2 + woff2 / 2) = o;
+        }
+    }
+}
+
+template <int CB>
+__global__ __launch_bounds__(64 * 8 / CB, CB == 2 ? 4 : 2) void lora_patch_multi_kernel(const PatchMultiEntry* __restrict__ plan, int n) {
+    typedef typename PatchVec<CB>::type vec;
     const int64_t tile = blockIdx.x;
     const PatchMultiEntry& E = plan[find_entry_multi(plan, n, tile)];
     const int out = E.d.out, in = E.d.in, na = E.d.n_adapters;
@@ -237,57 +429,66 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const P
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     const int r0 = tr * PT_ROWS;
-    const int c0 = tc * PT_COLS + wave * 128;
+    const int c0 = tc * PT_COLS + wave * (32 * CB);
     if (c0 >= in) return;
-    const int col = c0 + 4 * l32;
-    const bool full = (r0 + 32 <= out) && (c0 + 128 <= in) && ((in & 3) == 0);
-    f32x16 acc[4];
+    const int col = c0 + CB * l32;
+    const bool full = (r0 + 32 <= out) && (c0 + 32 * CB <= in) && ((in & 3) == 0);
+    if constexpr (CB == 4) {
+        bool all32 = full && (int64_t)out * in < (int64_t(1) << 30);
+#pragma unroll
+        for (int a = 0; a < SD_PATCH_MAX_ADAPTERS; ++a) all32 = all32 && (a >= na || E.d.r[a] == 32);
+        // (one or two adapters, the production norm; with three or four the straight line would
+        // need more registers than two wavefronts per SIMD leave, and the plain loop below serves)
+        if (all32 && na == 1) { patch_tile_rank32<1>(E, in, r0, col, l32, hi); return; }
+        if (all32 && na == 2) { patch_tile_rank32<2>(E, in, r0, col, l32, hi); return; }
+    }
+    f32x16 acc[CB];
     if (full) {
-        float4 w[16];
+        vec w[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
-            w[v] = NT_LOAD4(W + (size_t)row * in + col);
+            w[v] = nt_loadv<CB>(W + (size_t)row * in + col);
         }
         // W's old bits go out first, as one burst of stores, before any adapter's product
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
-            NT_STORE4(U + (size_t)row * in + col, w[v]);
+            nt_storev<CB>(U + (size_t)row * in + col, w[v]);
         }
 #pragma unroll 1
         for (int a = 0; a < na; ++a) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < CB; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-            delta_full(E.d.A[a], E.d.B[a], E.d.r[a], in, r0, col, l32, hi, acc);
+            delta_full_cb<CB>(E.d.A[a], E.d.B[a], E.d.r[a], in, r0, col, l32, hi, acc);
             const float scale = E.d.scale[a];
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                w[v].x = __fadd_rn(w[v].x, __fmul_rn(scale, acc[0][v]));
-                w[v].y = __fadd_rn(w[v].y, __fmul_rn(scale, acc[1][v]));
-                w[v].z = __fadd_rn(w[v].z, __fmul_rn(scale, acc[2][v]));
-                w[v].w = __fadd_rn(w[v].w, __fmul_rn(scale, acc[3][v]));
-            }
+            for (int v = 0; v < 16; ++v)
+#pragma unroll
+                for (int j = 0; j < CB; ++j) pv_at<CB>(w[v], j) = __fadd_rn(pv_at<CB>(w[v], j), __fmul_rn(scale, acc[j][v]));
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             const size_t idx = (size_t)row * in + col;
-            NT_STORE4(W + idx, w[v]);
+            nt_storev<CB>(W + idx, w[v]);
             if (S) {
-                bf16x4 o = {(__bf16)w[v].x, (__bf16)w[v].y, (__bf16)w[v].z, (__bf16)w[v].w};
-                *reinterpret_cast<bf16x4*>(S + idx) = o;
+                typedef __bf16 bvec __attribute__((ext_vector_type(CB)));
+                bvec o;
+#pragma unroll
+                for (int j = 0; j < CB; ++j) o[j] = (__bf16)pv_at<CB>(w[v], j);
+                *reinterpret_cast<bvec*>(S + idx) = o;
             }
         }
     } else {
-        float wv[16][4];
+        float wv[16][CB];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CB; ++j) {
                 const bool ok = row < out && col + j < in;
                 wv[v][j] = ok ? W[(size_t)row * in + col + j] : 0.f;
                 if (ok) U[(size_t)row * in + col + j] = wv[v][j];
@@ -296,22 +497,22 @@ __global__ __launch_bounds__(PT_THREADS, 2) void lora_patch_multi_kernel(const P
 #pragma unroll 1
         for (int a = 0; a < na; ++a) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < CB; ++j)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
-            delta_ragged(E.d.A[a], E.d.B[a], E.d.r[a], out, in, r0, col, l32, hi, acc);
+            delta_ragged_cb<CB>(E.d.A[a], E.d.B[a], E.d.r[a], out, in, r0, col, l32, hi, acc);
             const float scale = E.d.scale[a];
 #pragma unroll
             for (int v = 0; v < 16; ++v)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) wv[v][j] = __fadd_rn(wv[v][j], __fmul_rn(scale, acc[j][v]));
+                for (int j = 0; j < CB; ++j) wv[v][j] = __fadd_rn(wv[v][j], __fmul_rn(scale, acc[j][v]));
         }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = r0 + 8 * (v >> 2) + 4 * hi + (v & 3);
             if (row >= out) continue;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < CB; ++j) {
                 if (col + j >= in) continue;
                 const size_t idx = (size_t)row * in + col + j;
                 W[idx] = wv[v][j];
@@ -471,7 +672,7 @@ static int patch_multi_launch(bool undo, const void* plan_dev, int32_t n, int64_
     hipStream_t s = static_cast<hipStream_t>(stream);
     // (the multi-adapter patch kernel is held to fewer waves by its registers already)
     if (undo) hipLaunchKernelGGL(lora_unpatch_multi_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), UNPATCH_THROTTLE_LDS, s, plan, n);
-    else hipLaunchKernelGGL(lora_patch_multi_kernel, dim3((unsigned)total_tiles), dim3(PT_THREADS), 0, s, plan, n);
+    else hipLaunchKernelGGL((lora_patch_multi_kernel<4>), dim3((unsigned)total_tiles), dim3(PT_THREADS), 0, s, plan, n);
     SD_HIP_CHECK(hipGetLastError());
     return SD_OK;
 }

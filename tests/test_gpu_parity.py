@@ -484,8 +484,10 @@ def test_patch_several_adapters_one_pass(B):
     """Two and three adapters per matrix in one pass: the oracle's successive-patch chain, the
     bits of successive single-adapter launches, the bf16 serving copy, and the exact restore."""
     import torch
-    shapes = ((300, 200), (128, 128), (33, 1027), (640, 640), (64, 256))
-    ranks = ((32, 32), (32, 8, 5), (32,), (16, 32), (32, 32, 32, 32))
+    # (rank 32 throughout on tiles that lie inside the matrix takes a pipelined path of its own for
+    # one and for two adapters: 96 x 512 and 300 x 200 / 160 x 768 reach it)
+    shapes = ((300, 200), (128, 128), (33, 1027), (640, 640), (64, 256), (96, 512), (160, 768))
+    ranks = ((32, 32), (32, 8, 5), (32,), (16, 32), (32, 32, 32, 32), (32,), (32, 32))
     r = rng(21)
     host, devm, single = [], [], []
     for (o, i), rks in zip(shapes, ranks):
