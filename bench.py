@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 # known size (lora_unpatch): see profiles/lora_patch_hbm_traffic.txt
 PATCH_TRAFFIC_BYTES = 10.64e9   # FETCH_SIZE + WRITE_SIZE per patch launch, scaled (profiles/lora_patch_hbm_traffic.txt)
 # the same two counters for the kernels that can be the stack's dominant one (same file), bytes per launch
-STACK_TRAFFIC_BYTES = {"self_attention": 65.3e6, "ff1": 122.6e6}
+STACK_TRAFFIC_BYTES = {"self_attention": 59.8e6, "ff1": 142.9e6}
 
 
 def stack_flops(cfg) -> float:
