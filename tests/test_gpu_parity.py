@@ -148,11 +148,12 @@ def test_lora_linear_geglu_epilogue(B, M, C, F, rank):
     assert rel_err(O.geglu(np.concatenate([u[:, F:], u[:, :F]], 1)), ref) > 10 * BF16_TOL
 
 
-def test_lora_linear_geglu_large_ragged(B):
-    """Enough tiles for the 256-row GEGLU tile body (two rounds of the chip or more), with a
-    ragged last row tile, a ragged last column tile and a K that is not a multiple of 64."""
-    M, C, F, rank = 8192 + 77, 328, 2560 + 8, 16
-    r = rng(8269)
+@pytest.mark.parametrize("M,C,F,rank", [(8192 + 77, 328, 2560 + 8, 16), (8192, 328, 2560 - 8, 16), (8192 - 100, 64, 2560, 0)])
+def test_lora_linear_geglu_large_ragged(B, M, C, F, rank):
+    """Enough tiles for the 256-row GEGLU tile body (two rounds of the chip or more), with ragged
+    last row and column tiles and a K that is not a multiple of 64; with and without an adapter
+    (without one the launch has no down-projection tiles ahead of the 256x256 ones)."""
+    r = rng(M + F)
     p = mkproj(r, 2 * F, C, rank, bias=True, scale=0.5, w_std=0.08)
     x = G.bf16_round(r.standard_normal((M, C)).astype(np.float32))
     ref = O.geglu(O.lora_linear(x, p["W"], p["b"], p["A"], p["B"], p["scale"]))
@@ -160,8 +161,9 @@ def test_lora_linear_geglu_large_ragged(B):
     got = host(y)
     assert got.shape == (M, F)
     assert rel_err(got, ref) <= BF16_TOL
-    # the corners too, each on its own scale
-    for rows, cols in ((slice(0, 256), slice(0, 128)), (slice(M - 77, M), slice(F - 8, F)), (slice(M - 77, M), slice(0, 128))):
+    # corners and an interior band, each on its own scale
+    for rows, cols in ((slice(0, 256), slice(0, 128)), (slice(M - 77, M), slice(F - 8, F)), (slice(M - 77, M), slice(0, 128)),
+                       (slice(0, M), slice(2048 - 64, 2048 + 64)), (slice(M - 130, M), slice(2048, F))):
         assert rel_err(got[rows, cols], ref[rows, cols]) <= BF16_TOL
     assert B.gemm_dep_timeouts() == 0
 
