@@ -671,9 +671,12 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     int maxN = 0, maxK = 0;
     long t128 = 0;        // workgroup tiles at 128x128
     long t256 = 0;        // workgroup tiles of 256 rows x 128 output columns
+    long t64 = 0;         // workgroup tiles of 64 rows x 128 columns, down-projections aside
     bool res32 = false;   // some problem adds an fp32 residual: take the kernel that prefetches it
+    int n_main = 0;       // problems that are not down-projections
     for (int i = 0; i < g.n; ++i) {
         const GemmProblem& P = g.p[i];
+        if (!P.signal && P.Mp > 0 && P.N > 0) ++n_main;
         if (P.res && P.res_f32 && P.Mp > 0 && P.N > 0) res32 = true;
         SD_REQUIRE((P.geglu_F > 0) == geglu || P.signal, SD_EINVAL, "gemm group mixes GEGLU and plain problems");
         SD_REQUIRE(P.Mp >= 0 && P.N >= 0 && P.K0 > 0 && P.K0 % 8 == 0 && P.K1 >= 0 && P.K1 % 8 == 0, SD_EINVAL,
@@ -698,6 +701,7 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
         if (P.K0 > maxK) maxK = P.K0;
         t128 += (long)((P.Mp + 127) / 128) * ((P.N + 127) / 128);
         if (!P.signal) t256 += (long)((P.Mp + 255) / 256) * ((P.N + 127) / 128);
+        if (!P.signal) t64 += (long)((P.Mp + 63) / 64) * ((P.N + 127) / 128);
     }
     // drop empty problems
     int w = 0;
@@ -719,6 +723,13 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // ... except long-K launches (the feed-forward out-projection, K = 4C) that still give every CU
     // a 128x128 tile: over 40 k-steps the operand bytes per FLOP decide, not the ramps
     if (t128 < 1024 && !(maxK >= 2048 && t128 >= 256)) {
+        // at most two workgroups per CU anyway (2048 tokens): a third ring stage in the LDS the
+        // third workgroup would have used, -3 to -10 % per launch
+        if (t64 <= 512) {
+            if (geglu) return launch_cfg<64, 128, 64, 2, 2, 3, true, false>(g, guard, stream);
+            if (res32) return launch_cfg<64, 128, 64, 2, 2, 3, false, true>(g, guard, stream);
+            return launch_cfg<64, 128, 64, 2, 2, 3, false, false>(g, guard, stream);
+        }
         if (geglu) return launch_cfg<64, 128, 64, 2, 2, 2, true, false>(g, guard, stream);
         if (res32) return launch_cfg<64, 128, 64, 2, 2, 2, false, true>(g, guard, stream);
         return launch_cfg<64, 128, 64, 2, 2, 2, false, false>(g, guard, stream);
@@ -728,6 +739,10 @@ int launch_gemm_group(GemmGroup& g, hipStream_t stream) {
     // or more.  Half the operand bytes per FLOP from L2 and from LDS; measured 5 % faster per launch
     // than 128x128 in spite of the last, partly empty round (640 tiles on 256 CUs).
     if (geglu && t256 >= 512) return launch_cfg<256, 256, 64, 4, 2, 2, true, false>(g, guard, stream);
+    // One large plain projection with a long K loop (no launch of the transformer block: the
+    // 8192 x 4096 x 4096 yardstick runs at 1.18 PFLOP/s this way, 1.04 at 128x128).  Not for grouped
+    // launches: the q/k/v group with its short text-context problems loses a third.
+    if (!geglu && !res32 && n_main == 1 && t256 >= 512 && maxK >= 2048) return launch_cfg<256, 256, 64, 4, 2, 2, false, false>(g, guard, stream);
     if (geglu) return launch_cfg<128, 128, 64, 4, 2, 2, true, false>(g, guard, stream);
     if (res32) return launch_cfg<128, 128, 64, 4, 2, 2, false, true>(g, guard, stream);
     return launch_cfg<128, 128, 64, 4, 2, 2, false, false>(g, guard, stream);

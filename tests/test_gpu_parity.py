@@ -168,6 +168,23 @@ def test_lora_linear_geglu_large_ragged(B, M, C, F, rank):
     assert B.gemm_dep_timeouts() == 0
 
 
+@pytest.mark.parametrize("M,N,K,rank", [(8192 + 77, 2048 + 8, 2048 + 8, 16), (8192, 2048, 2048, 0)])
+def test_lora_linear_large_plain_projection(B, M, N, K, rank):
+    """One plain projection large enough for the 256x256 tile body (two rounds of the chip or more,
+    K >= 2048): ragged last row and column tiles and a ragged K with an adapter, exact tiles without."""
+    r = rng(M + N + K)
+    p = mkproj(r, N, K, rank, bias=True, scale=0.5, w_std=0.03)
+    x = G.bf16_round(r.standard_normal((M, K)).astype(np.float32))
+    ref = O.lora_linear(x, p["W"], p["b"], p["A"], p["B"], p["scale"])
+    got = host(B.lora_linear_fwd(dev(x, B), B.Proj.from_numpy(p)))
+    assert got.shape == (M, N)
+    assert rel_err(got, ref) <= BF16_TOL
+    for rows, cols in ((slice(0, 256), slice(0, 256)), (slice(M - 77, M), slice(N - 8, N)), (slice(M - 77, M), slice(0, 256)),
+                       (slice(0, M), slice(1024 - 64, 1024 + 64)), (slice(4096 - 3, 4096 + 3), slice(0, N))):
+        assert rel_err(got[rows, cols], ref[rows, cols]) <= BF16_TOL
+    assert B.gemm_dep_timeouts() == 0
+
+
 # ---------------------------------------------------------------------- attention_fwd
 def vt_layout(v, B):
     """[Bn, Tk, C] -> the transposed, per-sample padded layout [C, Bn * Tkp]."""
