@@ -469,6 +469,30 @@ def main() -> int:
 
     mfma_loop()
     cm = float(np.median(time_events(mfma_loop, 5)))
+    # vector-ALU issue rates (attention's other bound): one exponential in FMA slots, and whether
+    # exponentials and FMAs overlap (mixed / (exp + fma) = 1: one port, no overlap)
+    valu_ms, valu_n = [], []
+    for mode in range(3):
+        cnt = [None]
+
+        def valu_loop(mode=mode, cnt=cnt):
+            cnt[0] = B.ceiling_valu(cout, 1024, 4000, mode)
+
+        valu_loop()
+        valu_ms.append(float(np.median(time_events(valu_loop, 5))))
+        valu_n.append(cnt[0])
+    simds = 1024.0
+    exp_ns = valu_ms[0] * 1e6 * simds / valu_n[0][0]
+    fma_ns = valu_ms[1] * 1e6 * simds / valu_n[1][1]
+    # 16 exponentials dealt between the 4 MFMAs of the matrix-core loop's trip, 3 wavefronts per SIMD
+    # (attention's residency), against the MFMAs alone and the exponentials alone
+    B.ceiling_valu(cout, 768, 4000, 3)
+    t_both = float(np.median(time_events(lambda: B.ceiling_valu(cout, 768, 4000, 3), 5)))
+    t_mfma = float(np.median(time_events(lambda: B.ceiling_mfma_bf16(cout, 768, 4000), 5)))
+    t_exps = float(np.median(time_events(lambda: B.ceiling_valu(cout, 768, 8000, 0), 5)))
+    valu = {"v_fma_f32_ns_per_wave_instruction_per_simd": round(fma_ns, 3), "v_exp_f32_ns_per_wave_instruction_per_simd": round(exp_ns, 3),
+            "exp_in_fma_slots": round(exp_ns / fma_ns, 2), "mixed_over_sum_of_parts": round(valu_ms[2] / (valu_ms[0] + valu_ms[1]), 3),
+            "mfma4_exp16_trip_over_mfma4_trip": round(t_both / t_mfma, 3), "mfma4_exp16_trip_over_sum_of_parts": round(t_both / (t_mfma + t_exps), 3)}
     csrc = torch.randn(1 << 28, device="cuda")           # 1 GiB, well past the last-level cache
     cdst = torch.empty_like(csrc)
     B.ceiling_copy_f32(csrc, cdst)
@@ -493,6 +517,7 @@ def main() -> int:
     out["ceilings"] = {"mfma_bf16_tflops": round(mfma_ceiling, 1), "copy_f32_gbs": round(copy_ceiling, 1),
                        "copy_f32_gbs_at_patch_footprint": round(copy_large, 1),
                        "copy_1r2w_f32_gbs_at_patch_footprint": round(copy_1r2w, 1),
+                       "valu": valu,
                        "value_frac_of_mfma_ceiling": round(tflops / mfma_ceiling, 4),
                        "dominant_kernel_frac_of_mfma_ceiling": round(kernels[dom]["tflops"] / mfma_ceiling, 4)}
     if "patch" in out:

@@ -155,6 +155,15 @@ int sd_timing_disable(void);
  *   pointers, no overlap): 8 bytes of traffic per element. */
 int sd_ceiling_mfma_bf16(float* out, int32_t workgroups, int32_t iters, double* flops, void* stream);
 int sd_ceiling_copy_f32(const float* src, float* dst, size_t n, void* stream);
+/* ceiling_valu: `workgroups` x 4 wavefronts run `iters` trips over 8 independent register chains:
+ *   mode 0 one v_exp_f32 per chain and trip, mode 1 four v_fma_f32, mode 2 both, mode 3 two
+ *   exponentials per chain and trip dealt between the four MFMAs of ceiling_mfma_bf16's trip.  out as
+ *   for ceiling_mfma_bf16; *exps and *fmas (host, may be NULL) receive the wavefront-wide instruction
+ *   counts of the launch.  From the durations: what an exponential costs in FMA issue slots, whether
+ *   the two overlap, and how much of the exponentials runs under the MFMAs (mode 3 against
+ *   ceiling_mfma_bf16 with the same workgroups and iters): the vector-ALU side of the attention
+ *   kernel's bound. */
+int sd_ceiling_valu(float* out, int32_t workgroups, int32_t iters, int32_t mode, double* exps, double* fmas, void* stream);
 /* the same with two destinations (dst0 = dst1 = src afterwards): one read and two writes per element, the
  * traffic mix of the patch pass (W read, undo record and W' written) */
 int sd_ceiling_copy_1r2w_f32(const float* src, float* dst0, float* dst1, size_t n, void* stream);

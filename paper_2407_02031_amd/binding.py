@@ -83,6 +83,7 @@ def _load() -> C.CDLL:
         "sd_timing_disable": (C.c_int, []),
         "sd_ceiling_mfma_bf16": (C.c_int, [vp, i32, i32, P(C.c_double), vp]),
         "sd_ceiling_copy_f32": (C.c_int, [vp, vp, sz, vp]),
+        "sd_ceiling_valu": (C.c_int, [vp, i32, i32, i32, P(C.c_double), P(C.c_double), vp]),
         "sd_ceiling_copy_1r2w_f32": (C.c_int, [vp, vp, vp, sz, vp]),
         "sd_lora_linear_workspace_bytes": (sz, [i32, i32, i32, i32, i32]),
         "sd_lora_linear_fwd": (C.c_int, [vp, i32, P(sd_proj), vp, vp, f32, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]),
@@ -128,7 +129,7 @@ def _load() -> C.CDLL:
 
 
 _lib = _load()
-EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_set_projection_fusion", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32", "sd_ceiling_copy_1r2w_f32",
+EXPORTS = ["sd_last_error", "sd_version", "sd_gemm_dep_timeouts", "sd_set_projection_fusion", "sd_timing_enable", "sd_timing_collect", "sd_timing_disable", "sd_ceiling_mfma_bf16", "sd_ceiling_copy_f32", "sd_ceiling_copy_1r2w_f32", "sd_ceiling_valu",
            "sd_lora_linear_workspace_bytes", "sd_lora_linear_fwd", "sd_lora_linear_fwd_static",
            "sd_attn_block_workspace_bytes", "sd_attn_block_fwd", "sd_attention_workspace_bytes", "sd_attention_fwd", "sd_ff_block_workspace_bytes",
            "sd_ff_block_fwd", "sd_groupnorm_workspace_bytes", "sd_groupnorm_fwd", "sd_groupnorm_silu_fwd",
@@ -484,6 +485,13 @@ def ceiling_mfma_bf16(out: torch.Tensor, workgroups: int, iters: int) -> float:
     fl = C.c_double(0.0)
     _check(_lib.sd_ceiling_mfma_bf16(_ptr(out), workgroups, iters, C.byref(fl), _stream()))
     return fl.value
+
+
+def ceiling_valu(out: torch.Tensor, workgroups: int, iters: int, mode: int):
+    """Enqueue the vector-ALU issue loop; returns (exponentials, FMAs) of the launch, in wavefront-wide instructions."""
+    e, f = C.c_double(0.0), C.c_double(0.0)
+    _check(_lib.sd_ceiling_valu(_ptr(out), workgroups, iters, mode, C.byref(e), C.byref(f), _stream()))
+    return e.value, f.value
 
 
 def ceiling_copy_1r2w_f32(src: torch.Tensor, dst0: torch.Tensor, dst1: torch.Tensor) -> None:

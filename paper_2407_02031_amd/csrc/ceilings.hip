@@ -1,6 +1,6 @@
-// Two measured ceilings for the roofline figures, run on the same device as the kernels they
-// are compared with: a register-resident bf16 MFMA loop (no memory traffic at all) and a
-// streaming fp32 copy (one read and one write per element).  Vendor peaks assume the boost
+// Measured ceilings for the roofline figures, run on the same device as the kernels they
+// are compared with: a register-resident bf16 MFMA loop (no memory traffic at all), the issue
+// rates of the vector ALU, and a streaming fp32 copy (one read and one write per element).  Vendor peaks assume the boost
 // clock and ideal DRAM efficiency; these two say what this part sustains.
 #include "common.hpp"
 
@@ -34,6 +34,72 @@ __global__ __launch_bounds__(256) void ceiling_mfma_kernel(float* __restrict__ o
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
 }
 
+// Issue rates of the vector ALU, out of registers: MODE 0 a chain of v_exp_f32 per accumulator,
+// MODE 1 a chain of v_fma_f32, MODE 2 one exponential and four FMAs per accumulator and trip, MODE 3
+// two exponentials per accumulator and trip dealt between the four MFMAs of the matrix-core loop
+// above (same operands, same trip).  Eight independent accumulators per lane, so latency is covered
+// and the issue port is what is timed.  Attention's key loop leans on this port as much as on the
+// matrix cores: what an exponential costs in FMA slots and whether the two overlap decides whether a
+// polynomial on the FMA pipe could take exponentials off it; whether exponentials issue under
+// running MFMAs decides how much of them the key loop can hide at all.
+template <int MODE>
+__global__ __launch_bounds__(256) void ceiling_valu_kernel(float* __restrict__ out, int iters) {
+    float a[8], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = 0.25f + 1e-4f * (float)threadIdx.x + (float)i;
+        b[i] = 0.5f + (float)i;
+    }
+    if (MODE == 3) {
+        bf16x8 pa, pb;
+        uint32_t s = 0x9e3779b9u * (threadIdx.x + 1u) + blockIdx.x;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            s = s * 1664525u + 1013904223u;
+            pa[i] = (__bf16)(((int)(s >> 20) - 2048) * (1.0f / 4096.0f));
+            s = s * 1664525u + 1013904223u;
+            pb[i] = (__bf16)(((int)(s >> 20) - 2048) * (1.0f / 4096.0f));
+        }
+        f32x16 c[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) c[j][v] = 0.f;
+#pragma unroll 1
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                c[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, pb, c[j], 0, 0, 0);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[(j & 1) * 4 + i] = __builtin_amdgcn_exp2f(-__builtin_fabsf(a[(j & 1) * 4 + i]));
+            }
+        }
+        float r = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) r += c[j][0] + c[j][15];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r += a[i];
+        out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+        return;
+    }
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            // 2^-|a| stays in (0, 1]: a pure chain of exponentials (sign and magnitude are operand modifiers)
+            if (MODE == 0 || MODE == 2) a[i] = __builtin_amdgcn_exp2f(-__builtin_fabsf(a[i]));
+            if (MODE == 1 || MODE == 2) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[i] = __builtin_fmaf(b[i], 0.999f, 0.001f);
+            }
+        }
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r += a[i] + b[i];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = r;
+}
+
 constexpr int COPY_THREADS = 128;
 __global__ __launch_bounds__(COPY_THREADS) void ceiling_copy_kernel(const f32x4* __restrict__ src, f32x4* __restrict__ dst, size_t n4) {
     size_t i = (size_t)blockIdx.x * COPY_THREADS + threadIdx.x;
@@ -62,6 +128,21 @@ extern "C" int sd_ceiling_mfma_bf16(float* out, int32_t workgroups, int32_t iter
     hipLaunchKernelGGL(ceiling_mfma_kernel, dim3((unsigned)workgroups), dim3(256), 0, static_cast<hipStream_t>(stream), out, iters);
     SD_HIP_CHECK(hipGetLastError());
     if (flops) *flops = (double)workgroups * 4.0 /*waves*/ * iters * 4.0 /*MFMAs*/ * (2.0 * 32 * 32 * 16);
+    return SD_OK;
+}
+
+extern "C" int sd_ceiling_valu(float* out, int32_t workgroups, int32_t iters, int32_t mode, double* exps, double* fmas, void* stream) {
+    SD_REQUIRE(out && workgroups > 0 && iters > 0 && mode >= 0 && mode <= 3, SD_EINVAL, "ceiling_valu: out=%p workgroups=%d iters=%d mode=%d",
+               (void*)out, workgroups, iters, mode);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mode == 0) hipLaunchKernelGGL(ceiling_valu_kernel<0>, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters);
+    else if (mode == 1) hipLaunchKernelGGL(ceiling_valu_kernel<1>, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters);
+    else if (mode == 2) hipLaunchKernelGGL(ceiling_valu_kernel<2>, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters);
+    else hipLaunchKernelGGL(ceiling_valu_kernel<3>, dim3((unsigned)workgroups), dim3(256), 0, s, out, iters);
+    SD_HIP_CHECK(hipGetLastError());
+    const double groups = (double)workgroups * 4.0 /*waves*/ * iters * 8.0;   // wavefront-wide instructions: per accumulator and trip
+    if (exps) *exps = mode == 1 ? 0.0 : (mode == 3 ? 2.0 * groups : groups);
+    if (fmas) *fmas = (mode == 0 || mode == 3) ? 0.0 : 4.0 * groups;
     return SD_OK;
 }
 

@@ -593,6 +593,20 @@ def test_ceiling_copies_copy(B):
         assert torch.equal(d0, src) and torch.equal(d1, src) and torch.equal(d2, src), n
 
 
+def test_ceiling_valu_loop_runs_and_counts(B):
+    """The vector-ALU ceiling loop: instruction counts as documented, and a finite result in every
+    lane (2^-|a| chains stay in (0, 1], the FMA chains converge to 1)."""
+    import torch
+    out = torch.full((8 * 256,), float("nan"), device="cuda")
+    for mode, (e, f) in enumerate(((1, 0), (0, 4), (1, 4), (2, 0))):
+        exps, fmas = B.ceiling_valu(out, 8, 100, mode)
+        assert exps == e * 8 * 4 * 100 * 8 and fmas == f * 8 * 4 * 100 * 8
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out).all())
+    with pytest.raises(Exception):
+        B.ceiling_valu(out, 8, 100, 4)
+
+
 def test_bal_orders_the_patch_inside_a_denoising_loop(B):
     """The serving loop of Section 4.2 in miniature: a projection reads the bf16 serving copy of an
     fp32 master weight; two adapters load in the background (gated so that they arrive during
