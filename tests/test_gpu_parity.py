@@ -581,6 +581,42 @@ def test_controlnet_residual_add_bit_exact(B):
         B.controlnet_residual_add(xd[:n], [xd[n:2 * n]] * 9)
 
 
+def test_empty_inputs_are_no_ops(B):
+    """Zero rows, zero tokens, zero samples: every forward call returns without touching its
+    outputs (which are empty) and without an error; a later ordinary call still works."""
+    import torch
+    r = rng(7)
+    p = B.Proj.from_numpy(mkproj(r, 64, 32, 8, bias=True, scale=1.0))
+    e = torch.empty((0, 32), dtype=torch.bfloat16, device="cuda")
+    assert B.lora_linear_fwd(e, p).shape == (0, 64)
+    g = torch.ones(32, dtype=torch.bfloat16, device="cuda")
+    assert B.lora_linear_fwd(e, p, ln_gamma=g, ln_beta=g).shape == (0, 64)
+    C_, heads = 128, 2
+    pq, pk, pv, po = (B.Proj.from_numpy(mkproj(r, C_, C_, 8, bias=False, scale=1.0)) for _ in range(4))
+    gc = torch.ones(C_, dtype=torch.bfloat16, device="cuda")
+    for shape in ((0, 64, C_), (2, 0, C_)):
+        xe = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+        assert B.attn_block_fwd(xe, None, gc, gc, pq, pk, pv, po, heads).shape == shape
+        assert B.groupnorm_fwd(xe, gc, gc, 32).shape == shape
+    qe = torch.empty((2, 0, C_), dtype=torch.bfloat16, device="cuda")      # no queries against eight keys
+    k8 = torch.zeros((2, 8, C_), dtype=torch.bfloat16, device="cuda")
+    assert B.attention_fwd(qe, k8, torch.zeros((C_, 16), dtype=torch.bfloat16, device="cuda"), heads).shape == (2, 0, C_)
+    f1 = B.Proj.from_numpy(mkproj(r, 2 * 4 * C_, C_, 8, bias=True, scale=1.0))
+    f2 = B.Proj.from_numpy(mkproj(r, C_, 4 * C_, 8, bias=True, scale=1.0))
+    xe = torch.empty((0, C_), dtype=torch.bfloat16, device="cuda")
+    assert B.ff_block_fwd(xe, gc, gc, f1, f2).shape == (0, C_)
+    W = torch.zeros((64, 32), dtype=torch.bfloat16, device="cuda")
+    A = torch.zeros((8, 32), dtype=torch.bfloat16, device="cuda")
+    Bm = torch.zeros((64, 8), dtype=torch.bfloat16, device="cuda")
+    assert B.multi_lora_linear_fwd(e, W, None, [A], [Bm], [1.0], [0], [], out=None).shape == (0, 64)
+    torch.cuda.synchronize()
+    # and the library is in working order afterwards
+    x = G.bf16_round(r.standard_normal((40, 32)).astype(np.float32))
+    pn = mkproj(r, 64, 32, 8, bias=True, scale=1.0)
+    ref = O.lora_linear(x, pn["W"], pn["b"], pn["A"], pn["B"], pn["scale"])
+    assert rel_err(host(B.lora_linear_fwd(dev(x, B), B.Proj.from_numpy(pn))), ref) <= BF16_TOL
+
+
 def test_ceiling_copies_copy(B):
     """The streaming-ceiling kernels of the benchmark are plain copies: every byte arrives, sizes
     that are not a multiple of the grid's stride included."""
