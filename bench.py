@@ -200,6 +200,43 @@ def kernel_table(B, leg, K, ms_per_step):
     return kernels, per_step, round(tagged, 3)
 
 
+def vendor_gemm_context():
+    """torch.matmul (bf16, [M, K] x [N, K]^T) on the shapes of ff1, q/k/v, an N = 640 projection and ff2 at config 2."""
+    import numpy as np
+    import torch
+    res = {"what": "torch.matmul bf16, plain GEMM, 30 launches per graph replay, median of 5 replays", "us": {}, "tflops": {}}
+    for name, (M, N, K) in (("ff1_8192x5120x704", (8192, 5120, 704)), ("qkv_8192x1920x704", (8192, 1920, 704)),
+                            ("proj_8192x640x704", (8192, 640, 704)), ("ff2_8192x640x2624", (8192, 640, 2624))):
+        a = torch.randn(M, K, device="cuda").to(torch.bfloat16)
+        b = torch.randn(N, K, device="cuda").to(torch.bfloat16)
+        c = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        for _ in range(5):
+            torch.matmul(a, b.t(), out=c)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(30):
+                    torch.matmul(a, b.t(), out=c)
+        g.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(5):
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) / 30)
+        ms = float(np.median(ts))
+        res["us"][name] = round(ms * 1e3, 1)
+        res["tflops"][name] = round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
+        del g, a, b, c
+    return res
+
+
 def stack_leg_report(B, leg, K, W, use_graph):
     cfg = leg.cfg
     ms, groups, launch = time_steps([leg.step], K, W, use_graph)
@@ -219,6 +256,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-patch", action="store_true")
+    ap.add_argument("--no-vendor-context", action="store_true", help="skip the vendor GEMM library timings (context only)")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the legs for the tiny and the 32x32 configuration")
     ap.add_argument("--no-graph", action="store_true", help="launch every step kernel by kernel instead of replaying a HIP graph")
     args = ap.parse_args()
@@ -572,6 +610,16 @@ def main() -> int:
                                "sample": "%d pass(es) of patch + unpatch over every tenth matrix (31 matrices, %.0f M elements; 12 + 8 B per element), %.1f s"
                                          % (calls, pel / 1e6, dt)}
         out["cpu_baselines_other_workloads"] = more
+    # ------------------------------------------------------------ vendor library, context only
+    # What the vendor's GEMM library (through torch.matmul) reaches on this machine on the plain GEMMs
+    # underneath the block's largest projections: no LayerNorm, adapter, GEGLU or residual.  Not a
+    # target and not part of the product path; it says how far the shapes themselves are from the
+    # matrix cores' peak.
+    if not args.no_vendor_context:
+        try:
+            out["vendor_library_context"] = vendor_gemm_context()
+        except Exception as e:   # the library is not ours: report, do not fail the benchmark
+            out["vendor_library_context"] = {"error": str(e)[:200]}
     out["context"] = "paper reports up to 7.8x latency / 1.6x throughput for SDXL end to end on H800; no kernel-level figure"
     print(json.dumps(out))
     return 0
